@@ -1,0 +1,174 @@
+/*
+ * libaweq -- AWEQ (arXiv 2311.01305) per-linear-layer calibration + quantization path
+ * for AMD MI355X (gfx950).  C ABI.
+ *
+ * Notation (the paper's): X[T x K] calibration activations (T tokens, K input channels),
+ * W[N x K] the linear weight in PyTorch layout (the paper writes Y = X W with W as K x N,
+ * Sec. 3.1 Eq. 3; its "channel i" is the column index k of both X and W here),
+ * s[K] the equalization factors, Step / Z the quantizer's scale and zero point (Eq. 1-2).
+ *
+ * Conventions for every entry point
+ *   - every pointer is a DEVICE pointer owned by the caller, unless marked "host";
+ *     matrices are row-major with the K index contiguous and a leading dimension in
+ *     elements; rows must start 16-byte aligned;
+ *   - the library allocates nothing, frees nothing and never synchronises: each call
+ *     enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and returns; scratch memory comes from the caller (`ws`, `ws_bytes`; ask
+ *     aweq_workspace_size), and may be reused by the next call on the same stream;
+ *   - the return value is 0 or a negative AWEQ_ERR_* code found on the HOST before
+ *     anything is launched (bad pointer, shape, dtype, alignment, workspace);
+ *   - numeric conditions met on the device are OR-ed into the optional device word
+ *     `status` (AWEQ_ST_* bits); inputs are expected to be finite;
+ *   - calls on different streams must not share output or workspace buffers.
+ */
+#ifndef AWEQ_H
+#define AWEQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { AWEQ_F32 = 0, AWEQ_F16 = 1, AWEQ_I8 = 2 } aweq_dtype;
+
+enum {
+    AWEQ_OK = 0,
+    AWEQ_ERR_NULL = -1,      /* a required pointer is NULL */
+    AWEQ_ERR_SHAPE = -2,     /* a dimension is <= 0, a leading dimension is too small, K % 8 != 0 */
+    AWEQ_ERR_DTYPE = -3,     /* dtype not supported by this entry point */
+    AWEQ_ERR_BITS = -4,      /* bits not in {8, 4, 3} */
+    AWEQ_ERR_GROUP = -5,     /* group does not divide K or is not a supported size */
+    AWEQ_ERR_ALIGN = -6,     /* a pointer or row pitch is not 16-byte aligned */
+    AWEQ_ERR_WORKSPACE = -7, /* ws is NULL or smaller than aweq_workspace_size says */
+    AWEQ_ERR_LAUNCH = -8     /* the HIP runtime refused a launch */
+};
+
+/* bits of the device status word */
+enum {
+    AWEQ_ST_DEGENERATE = 1u, /* Eq. 2 gave a non-positive or non-finite Step; Step := 1 was used */
+    AWEQ_ST_NONFINITE = 2u,  /* NaN / Inf seen in the input (results unspecified) */
+    AWEQ_ST_BIGQUOT = 4u,    /* |x / Step| >= 2^24: quotient saturated */
+    AWEQ_ST_SCALEGUARD = 8u  /* Eq. 10: a channel range was < 1e-5 (s := 1) or s was clamped to [1e-4, 1e4] */
+};
+
+typedef enum {
+    AWEQ_OP_CALIB_STATS = 0,
+    AWEQ_OP_EQUALIZE = 1,
+    AWEQ_OP_QUANT_WEIGHT = 2,
+    AWEQ_OP_W8A8_GEMM = 3,
+    AWEQ_OP_BIAS_CORRECT = 4
+} aweq_op;
+
+enum { AWEQ_BIAS_W8A8 = 0, AWEQ_BIAS_WEIGHT_ONLY = 1 };
+
+/* Bytes of workspace the op needs for a [rows x K] input (rows = T or N as the op reads
+ * it) and N output channels; 0 when it needs none.  Host function, no GPU needed. */
+size_t aweq_workspace_size(aweq_op op, int64_t rows, int64_t K, int64_t N);
+
+/* Name of an AWEQ_ERR_* code.  Host function. */
+const char* aweq_status_string(int code);
+
+/* ---- Stage 1: range statistics (Sec. 3.2: channel range = channel max - channel min,
+ * tensor range = max - min over all channels, Eq. 4 p_i = r_i / R; Sec. 3.3: E[x] is
+ * collected in the same pass).
+ * M[rows x K] (F32 or F16, pitch ld) -> cmin[K], cmax[K] (exact), csum[K] (fp64 column
+ * sums, nullable), count (uint64 scalar, nullable).  accumulate = 0 starts from
+ * (+inf, -inf, 0, 0); accumulate = 1 merges into what the buffers hold (further
+ * calibration batches; or a second weight sharing the same input: min of mins, max of
+ * maxes).  finalize = 1 also writes r[K] = cmax - cmin, R[1] = max_k cmax - min_k cmin and
+ * (nullable) p[K] = r / R.  Needs workspace. */
+int aweq_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int64_t ld,
+                     float* cmin, float* cmax, double* csum, uint64_t* count,
+                     int accumulate, int finalize, float* r, float* R, float* p,
+                     void* ws, size_t ws_bytes, uint32_t* status, void* stream);
+
+/* ---- Stage 2: activation-weight equalization (Sec. 3.1 Eq. 3, Sec. 3.2 Eq. 10).
+ * From the column statistics of X (xmin, xmax, xsum, host scalar count = T) and of W
+ * (wmin, wmax): s[k] = sqrt(r_x r_w) / r_w evaluated in fp64 on the raw channel ranges,
+ * inv_s[k] = 1 / s[k]  (enable_awe = 0: s = 1, the ablation switch of Sec. 4.4).
+ * Guards: a channel with r_x < 1e-5 or r_w < 1e-5 gets s = 1; s is clamped to [1e-4, 1e4].
+ * Fold, weight side: W_hat[n,k] = W[n,k] * s[k], one fp32 multiply rounded to dt
+ * (W_hat may alias W; W = NULL skips the fold).  Activation side: the equalised
+ * activation X_hat[t,k] = X[t,k] * inv_s[k] is never stored; its tensor range
+ * xhat_range[2] = {min, max}, its mean mu_xhat[K] = (xsum / count) * inv_s and the static
+ * int8 activation quantizer derived from that range by Eq. 2 (act_step[1], act_zero[1])
+ * are written instead.  prev_scale[K] (nullable) is multiplied by inv_s so the caller can
+ * fuse diag(s)^-1 into the preceding block.  mu_xhat / xsum nullable together. */
+int aweq_equalize(const float* xmin, const float* xmax, const double* xsum, uint64_t count,
+                  const float* wmin, const float* wmax, int64_t K, int enable_awe,
+                  float* s, float* inv_s,
+                  const void* W, void* W_hat, aweq_dtype dt, int64_t N, int64_t ldw,
+                  float* prev_scale, float* xhat_range, float* mu_xhat,
+                  float* act_step, int32_t* act_zero,
+                  uint32_t* status, void* stream);
+
+/* ---- Stage 3: weight quantizer, Eq. 1-2: Step = (max - min) / (2^b - 1),
+ * Z = -round(min / Step), u = clamp(round(w / Step) + Z, 0, 2^b - 1); round-to-nearest
+ * with ties to even, true fp32 division.  A slice with max == min uses Step = 1.
+ * group = 0: one (Step, Z) per row n -> step[N], zero[N];
+ * group = g > 0 (a power of two in [8, 512] dividing K): one per g consecutive k inside a
+ *   row -> step/zero[N x K/g];
+ * group = -1: one for the whole tensor -> step[1], zero[1] (needs workspace).
+ * codes: bits 8 -> int8 u - 128, N*K bytes; bits 4 -> two codes per byte, even k in the
+ * low nibble, N*K/2 bytes; bits 3 -> per row a little-endian bit stream with code k in bits
+ * [3k, 3k+3), N*3K/8 bytes (K % 32 == 0).  rowsum_w[N] = sum_k (u - 128), bits 8 only,
+ * nullable. */
+int aweq_quant_weight(const void* W_hat, aweq_dtype dt, int64_t N, int64_t K, int64_t ldw,
+                      int bits, int group, void* codes, float* step, int32_t* zero,
+                      int32_t* rowsum_w, void* ws, size_t ws_bytes,
+                      uint32_t* status, void* stream);
+
+/* ---- Stage 4a (helper, also run by aweq_w8a8_gemm): static per-tensor int8 activation
+ * quantizer (Eq. 1 with b = 8) applied to X_hat = X * inv_s on the fly:
+ * xq[t,k] = clamp(round((X[t,k] * inv_s[k]) / Step_x) + Z_x, 0, 255) - 128,
+ * rowsum_x[T] = sum_k xq (int32, nullable), colsum_xq[K] = sum_t xq (int64, nullable).
+ * act_step / act_zero are the device scalars aweq_equalize wrote. */
+int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx,
+                   const float* inv_s, const float* act_step, const int32_t* act_zero,
+                   int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
+                   uint32_t* status, void* stream);
+
+/* ---- Stage 4: W8A8 forward (Sec. 1-2: INT8 weights and activations).
+ * x_dt F16 / F32: X is quantised into xq[T x K] first (stage 4a; xq, inv_s, act_step,
+ * act_zero required).  x_dt I8: X already holds xq, stage 4a is skipped.
+ * acc[t,n] = sum_k xq[t,k] wq[n,k], int8 x int8 -> int32 on the matrix cores.
+ * Outputs, each nullable: out_i32[T x N] (pitch ldo) the raw accumulator;
+ * out_deq[T x N] (F16 or F32, pitch ldo) the de-quantised output
+ *   Step_x Step_w[n] (acc - Z'x rowsum_w[n] - Z'w[n] rowsum_x[t] + K Z'x Z'w[n]) + bias[n],
+ *   Z' = Z - 128 (needs rowsum_x, rowsum_w, step_w, zero_w; bias nullable);
+ * colsum_acc[N] = sum_t acc[t,n] (int64; what stage 5 needs). */
+int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t K, int64_t ldx,
+                   const float* inv_s, const float* act_step, const int32_t* act_zero,
+                   int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
+                   const int8_t* wq, int64_t N, const float* step_w, const int32_t* zero_w,
+                   const int32_t* rowsum_w, const float* bias,
+                   int32_t* out_i32, void* out_deq, aweq_dtype out_dt, int64_t ldo,
+                   int64_t* colsum_acc, void* ws, size_t ws_bytes,
+                   uint32_t* status, void* stream);
+
+/* ---- Stage 5: quantization bias correction (Sec. 3.3, Eq. 11-15).
+ * delta[n] = mean over the calibration tokens of the FP output of the equalised layer
+ * minus the mean output of the quantised layer; bias_out = bias_in + delta (the paper
+ * subtracts E[y~ - y]).  enable_bc = 0 still writes delta but copies the bias unchanged.
+ * mode AWEQ_BIAS_W8A8: mean FP output = W_hat mu_xhat (fp64 accumulation); mean int8-path
+ *   output from colsum_acc, colsum_xq, rowsum_w, act_step/act_zero, step_w/zero_w[N]
+ *   (exact integers), count = T.
+ * mode AWEQ_BIAS_WEIGHT_ONLY (Eq. 12-15): delta[n] = -sum_k (W~[n,k] - W_hat[n,k]) mu_xhat[k]
+ *   with W~ de-quantised from codes / bits / group / step_w / zero_w as laid out by
+ *   aweq_quant_weight.
+ * bias_in nullable (= zeros); delta, bias_out fp32[N]. */
+int aweq_bias_correct(int mode, const void* W_hat, aweq_dtype dt, int64_t N, int64_t K, int64_t ldw,
+                      const float* mu_xhat, uint64_t count,
+                      const int64_t* colsum_acc, const int64_t* colsum_xq, const int32_t* rowsum_w,
+                      const float* act_step, const int32_t* act_zero,
+                      const void* codes, int bits, int group,
+                      const float* step_w, const int32_t* zero_w,
+                      const float* bias_in, float* delta, float* bias_out, int enable_bc,
+                      void* ws, size_t ws_bytes, uint32_t* status, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AWEQ_H */

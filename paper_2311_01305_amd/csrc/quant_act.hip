@@ -1,0 +1,244 @@
+// Stage 4a: static per-tensor int8 activation quantizer (Sec. 2, Eq. 1 with b = 8) applied
+// to the equalised activation X_hat = X diag(s)^-1 (Sec. 3.1, Eq. 3) on the fly, with the
+// per-token and per-channel code sums the GEMM epilogue and the bias correction need.
+//
+// HBM-bound (2 bytes in, 1 byte out per element for binary16) with a tight ALU budget, so
+// the quotient x / Step is formed without the generic division sequence when that is
+// provably the same: Step is one constant, y = RN(1 / Step) is computed once, and
+//   q0 = RN(a y);  r = a - Step q (exact, FMA);  q = RN(q + r y)   applied twice
+// gives the correctly rounded a / Step.  After the first correction q is within
+// 1/2 + 2^-22 ulp of a / Step; a quotient of two binary32 numbers is at least
+// 2^-25 / beta ulp away from a rounding boundary (beta = significand(Step) / 2^24 < 1),
+// while the second correction's error is below (1/2 + 2^-22) beta 2^-24 ulp, which is
+// smaller whenever beta <= 1 - 2^-20.  Steps with a significand above that, exponents
+// outside [-60, 60], zero points beyond 2^23 and binary32 inputs take the true division.
+#include "common.hpp"
+
+namespace aweq {
+
+constexpr int kQaBlock = 256;
+constexpr int kQaWaves = kQaBlock / kWave;
+constexpr int kQaVpt = 2;                               // units (8 columns) per thread per row
+constexpr int kQaChunk = kQaBlock * 8 * kQaVpt;         // 4096 columns per block
+constexpr int kQaMaxRows = 512;                         // rows per block (LDS row-sum slots)
+constexpr int kQaRowBatch = 4;                          // rows in flight per thread
+
+struct ActParams {
+    float step, rstep, lo_f, hi_f;
+    int zero, zoff;
+    bool fast;
+};
+
+__device__ __forceinline__ ActParams act_params(const float* act_step, const int32_t* act_zero, bool f16)
+{
+    ActParams p;
+    p.step = *act_step;
+    p.zero = *act_zero;
+    p.rstep = 1.0f / p.step;
+    const uint32_t b = __float_as_uint(p.step);
+    const int e = (int)((b >> 23) & 0xff) - 127;
+    const uint32_t m = b & 0x7fffffu;
+    p.fast = f16 && (b >> 31) == 0 && e >= -60 && e <= 60 && m < 0x7ffff0u && p.zero > -(1 << 23) && p.zero < (1 << 23);
+    p.lo_f = (float)(-p.zero);
+    p.hi_f = (float)(255 - p.zero);
+    p.zoff = p.zero - 128;
+    return p;
+}
+
+// stored code q = clamp(round(a / Step) + Z, 0, 255) - 128 for one value
+template <bool FAST>
+__device__ __forceinline__ int act_code(float a, const ActParams& p, float& big, uint32_t& st)
+{
+    if constexpr (FAST) {
+        float q = a * p.rstep;
+        float r = __builtin_fmaf(-p.step, q, a);
+        q = __builtin_fmaf(r, p.rstep, q);
+        r = __builtin_fmaf(-p.step, q, a);
+        q = __builtin_fmaf(r, p.rstep, q);
+        const float n = rintf(q);
+        big = fmaxf(big, fabsf(n));
+        // |Z| < 2^23: the clamp can be taken on the (integral) float before the conversion
+        return (int)__builtin_amdgcn_fmed3f(n, p.lo_f, p.hi_f) + p.zoff;
+    } else {
+        return quant_div(a, p.step, p.zero, 255, st) - 128;
+    }
+}
+
+template <bool F16, bool FAST>
+__device__ __forceinline__ void act_unit(const float x[8], const float is[8], const ActParams& p, int8_t* dst,
+                                         int cs[8], int& rs, float& big, uint32_t& st)
+{
+    int c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float a = x[i] * is[i];
+        c[i] = act_code<FAST>(a, p, big, st);
+        cs[i] += c[i];
+    }
+    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        w0 |= (uint32_t)(c[i] & 0xff) << (8 * i);
+        w1 |= (uint32_t)(c[4 + i] & 0xff) << (8 * i);
+    }
+    rs = __builtin_amdgcn_sdot4((int)w0, 0x01010101, rs, false);
+    rs = __builtin_amdgcn_sdot4((int)w1, 0x01010101, rs, false);
+    *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
+}
+
+template <bool F16>
+__device__ __forceinline__ void load_unit8(const void* X, int64_t elt, float x[8])
+{
+    if constexpr (F16) {
+        Half8 v = *reinterpret_cast<const Half8*>(reinterpret_cast<const _Float16*>(X) + elt);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float2 f = h2f2(v.h[i]);
+            x[2 * i] = f.x;
+            x[2 * i + 1] = f.y;
+        }
+    } else {
+        const float* p = reinterpret_cast<const float*>(X) + elt;
+        Float4 a = *reinterpret_cast<const Float4*>(p), b = *reinterpret_cast<const Float4*>(p + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[i] = a.f[i]; x[4 + i] = b.f[i]; }
+    }
+}
+
+// grid (column chunks of 4096, row slices); every block owns full 4096-column strips of its
+// rows, the four wavefronts side by side along K.
+template <bool F16>
+__global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
+    const void* __restrict__ X, int64_t T, int64_t K, int64_t ldx, const float* __restrict__ inv_s,
+    const float* __restrict__ act_step, const int32_t* __restrict__ act_zero, int8_t* __restrict__ xq,
+    int32_t* __restrict__ rowsum_x, long long* __restrict__ colsum_xq, int rows_per_block, int multi_chunk,
+    uint32_t* status)
+{
+    __shared__ int lds_rs[kQaMaxRows][kQaWaves];
+    __shared__ int lds_cs[kQaChunk];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t col0 = (int64_t)blockIdx.x * kQaChunk;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    const int nrows = (int)min((int64_t)rows_per_block, T - r0);
+    const ActParams p = act_params(act_step, act_zero, F16);
+
+    int64_t col[kQaVpt];
+    bool valid[kQaVpt];
+    float is[kQaVpt][8];
+    int cs[kQaVpt][8];
+    bool fast = p.fast;
+#pragma unroll
+    for (int j = 0; j < kQaVpt; ++j) {
+        col[j] = col0 + ((int64_t)threadIdx.x + j * kQaBlock) * 8;
+        valid[j] = col[j] < K;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            is[j][i] = valid[j] ? inv_s[col[j] + i] : 1.0f;
+            cs[j][i] = 0;
+            // the exactness argument needs a y not to overflow: binary16 |x| < 2^16, Step >= 2^-60
+            if (!(fabsf(is[j][i]) < 1.0e12f)) fast = false;
+        }
+    }
+    uint32_t st = 0;
+    float big = 0.0f;
+
+    for (int rb = 0; rb < nrows; rb += kQaRowBatch) {
+        float x[kQaRowBatch][kQaVpt][8];
+#pragma unroll
+        for (int b = 0; b < kQaRowBatch; ++b)
+#pragma unroll
+            for (int j = 0; j < kQaVpt; ++j)
+                if (rb + b < nrows && valid[j]) load_unit8<F16>(X, (r0 + rb + b) * ldx + col[j], x[b][j]);
+#pragma unroll
+        for (int b = 0; b < kQaRowBatch; ++b) {
+            if (rb + b >= nrows) break;
+            int rs = 0;
+#pragma unroll
+            for (int j = 0; j < kQaVpt; ++j)
+                if (valid[j]) {
+                    int8_t* dst = xq + (r0 + rb + b) * K + col[j];
+                    if (fast) act_unit<F16, true>(x[b][j], is[j], p, dst, cs[j], rs, big, st);
+                    else act_unit<F16, false>(x[b][j], is[j], p, dst, cs[j], rs, big, st);
+                }
+            rs = wave_allreduce(rs, OpAdd());
+            if (lane == 0) lds_rs[rb + b][wave] = rs;
+        }
+    }
+    if (big >= 16777216.0f) st |= AWEQ_ST_BIGQUOT;
+    raise_status(status, st);
+
+#pragma unroll
+    for (int j = 0; j < kQaVpt; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lds_cs[(threadIdx.x + j * kQaBlock) * 8 + i] = cs[j][i];
+    __syncthreads();
+    if (rowsum_x)
+        for (int i = threadIdx.x; i < nrows; i += kQaBlock) {
+            int tot = 0;
+#pragma unroll
+            for (int w = 0; w < kQaWaves; ++w) tot += lds_rs[i][w];
+            if (multi_chunk) atomicAdd(&rowsum_x[r0 + i], tot);
+            else rowsum_x[r0 + i] = tot;
+        }
+    if (colsum_xq)
+        for (int c = threadIdx.x; c < kQaChunk; c += kQaBlock) {
+            const int64_t k = col0 + c;
+            if (k < K) atomicAdd(reinterpret_cast<unsigned long long*>(&colsum_xq[k]), (unsigned long long)(long long)lds_cs[c]);
+        }
+}
+
+__global__ void zero_fill_u32(uint32_t* p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+int launch_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx, const float* inv_s,
+                     const float* act_step, const int32_t* act_zero, int8_t* xq, int32_t* rowsum_x,
+                     int64_t* colsum_xq, uint32_t* status, hipStream_t st)
+{
+    const int chunks = (int)cdiv(K, kQaChunk);
+    int64_t slices = cdiv(4096, chunks);
+    int64_t rpb = cdiv(T, slices);
+    rpb = cdiv(rpb, kQaRowBatch) * kQaRowBatch;
+    if (rpb > kQaMaxRows) rpb = kQaMaxRows;
+    slices = cdiv(T, rpb);
+    if (slices > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+    const int multi = chunks > 1;
+    // the accumulating outputs start from zero (a fill kernel, so the call can be graph-captured)
+    if (colsum_xq) zero_fill_u32<<<(unsigned)cdiv(2 * K, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_xq), 2 * K);
+    if (rowsum_x && multi) zero_fill_u32<<<(unsigned)cdiv(T, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(rowsum_x), T);
+    dim3 grid(chunks, (unsigned)slices);
+    if (dt == AWEQ_F16)
+        quant_act_kernel<true><<<grid, kQaBlock, 0, st>>>(X, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x,
+                                                          reinterpret_cast<long long*>(colsum_xq), (int)rpb, multi, status);
+    else
+        quant_act_kernel<false><<<grid, kQaBlock, 0, st>>>(X, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x,
+                                                           reinterpret_cast<long long*>(colsum_xq), (int)rpb, multi, status);
+    return launch_status();
+}
+
+int check_quant_act_args(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx, const float* inv_s,
+                         const float* act_step, const int32_t* act_zero, const int8_t* xq)
+{
+    if (!X || !inv_s || !act_step || !act_zero || !xq) return AWEQ_ERR_NULL;
+    if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
+    if (T <= 0 || K <= 0 || ldx < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
+    if (!aligned16(X) || ((size_t)ldx * dtype_size(dt)) % 16 != 0 || !aligned16(xq)) return AWEQ_ERR_ALIGN;
+    return AWEQ_OK;
+}
+
+}  // namespace aweq
+
+using namespace aweq;
+
+extern "C" int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx,
+                              const float* inv_s, const float* act_step, const int32_t* act_zero,
+                              int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
+                              uint32_t* status, void* stream)
+{
+    const int rc = check_quant_act_args(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq);
+    if (rc != AWEQ_OK) return rc;
+    return launch_quant_act(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, status, as_stream(stream));
+}

@@ -1,0 +1,290 @@
+// Stage 1: per-channel minimum / maximum / sum of a tall row-major matrix
+// (Sec. 3.2: channel range and tensor range; Sec. 3.3: E[x] collected alongside).
+//
+// HBM-bound streaming pass.  Lanes own columns (16 bytes = 8 halves or 4 floats per lane),
+// so a wavefront reads 1 KiB contiguous per row; the four wavefronts of a block take
+// interleaved rows of one row slice and meet in LDS; each block writes one partial row of
+// (min, max, sum) to the workspace, and a second small kernel folds the slices in a fixed
+// order (so the fp64 sums are reproducible) and merges with earlier batches.
+#include "common.hpp"
+
+namespace aweq {
+
+constexpr int kStatsBlock = 256;
+constexpr int kStatsWaves = kStatsBlock / kWave;
+constexpr int kRowBatch = 8;  // rows summed in fp32 before one fp64 add (binary16 input only)
+
+struct StatsPlan {
+    int col_chunks;   // blocks along K
+    int slices;       // row slices
+    int64_t rows_per_slice;
+};
+
+// Same plan on the host for the launch and for the workspace size.
+inline StatsPlan stats_plan(int64_t rows, int64_t K, int elts_per_lane)
+{
+    StatsPlan p;
+    const int64_t cols_per_block = (int64_t)kWave * elts_per_lane;
+    p.col_chunks = (int)cdiv(K, cols_per_block);
+    int64_t want = cdiv(2560, p.col_chunks);           // ~10 blocks per compute unit (5 resident)
+    int64_t max_slices = cdiv(rows, kStatsWaves * kRowBatch);  // at least one row batch per wavefront
+    if (want > max_slices) want = max_slices;
+    if (want < 1) want = 1;
+    p.rows_per_slice = cdiv(cdiv(rows, want), kStatsWaves * kRowBatch) * (kStatsWaves * kRowBatch);
+    p.slices = (int)cdiv(rows, p.rows_per_slice);
+    return p;
+}
+
+inline size_t stats_ws_bytes(int64_t rows, int64_t K)
+{
+    // sized for the narrower lane width (more chunks never increases the slice count)
+    StatsPlan a = stats_plan(rows, K, 8), b = stats_plan(rows, K, 4);
+    int s = a.slices > b.slices ? a.slices : b.slices;
+    return (size_t)s * (size_t)K * (sizeof(float) * 2 + sizeof(double));
+}
+
+// ---- binary16: 8 columns per lane
+__global__ __launch_bounds__(kStatsBlock) void col_stats_partial_f16(
+    const _Float16* __restrict__ M, int64_t rows, int64_t K, int64_t ld, int64_t rows_per_slice,
+    float* __restrict__ pmin, float* __restrict__ pmax, double* __restrict__ psum)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t col = ((int64_t)blockIdx.x * kWave + lane) * 8;
+    const bool active = col < K;
+    const int64_t r_begin = (int64_t)blockIdx.y * rows_per_slice;
+    const int64_t r_end = min(rows, r_begin + rows_per_slice);
+
+    const f16x2 pinf = {(_Float16)INFINITY, (_Float16)INFINITY};
+    const f16x2 ninf = {(_Float16)-INFINITY, (_Float16)-INFINITY};
+    f16x2 mn[4] = {pinf, pinf, pinf, pinf};
+    f16x2 mx[4] = {ninf, ninf, ninf, ninf};
+    double sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    if (active) {
+        const _Float16* base = M + col;
+        // wavefront w takes rows r_begin + w, + kStatsWaves, ...; kRowBatch rows in flight
+        int64_t r = r_begin + wave;
+        for (; r + (int64_t)(kRowBatch - 1) * kStatsWaves < r_end; r += (int64_t)kRowBatch * kStatsWaves) {
+            Half8 v[kRowBatch];
+#pragma unroll
+            for (int j = 0; j < kRowBatch; ++j)
+                v[j] = *reinterpret_cast<const Half8*>(base + (r + (int64_t)j * kStatsWaves) * ld);
+            float part[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < kRowBatch; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    mn[i] = hmin2(mn[i], v[j].h[i]);
+                    mx[i] = hmax2(mx[i], v[j].h[i]);
+                    float2 f = h2f2(v[j].h[i]);
+                    part[2 * i] += f.x;
+                    part[2 * i + 1] += f.y;
+                }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sum[i] += (double)part[i];
+        }
+        for (; r < r_end; r += kStatsWaves) {
+            Half8 v = *reinterpret_cast<const Half8*>(base + r * ld);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                mn[i] = hmin2(mn[i], v.h[i]);
+                mx[i] = hmax2(mx[i], v.h[i]);
+                float2 f = h2f2(v.h[i]);
+                sum[2 * i] += (double)f.x;
+                sum[2 * i + 1] += (double)f.y;
+            }
+        }
+    }
+
+    // cross-wavefront combine in LDS: [wave][lane][8]
+    __shared__ float s_mn[kStatsWaves][kWave][8];
+    __shared__ float s_mx[kStatsWaves][kWave][8];
+    __shared__ double s_sm[kStatsWaves][kWave][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float2 a = h2f2(mn[i]), b = h2f2(mx[i]);
+        s_mn[wave][lane][2 * i] = a.x; s_mn[wave][lane][2 * i + 1] = a.y;
+        s_mx[wave][lane][2 * i] = b.x; s_mx[wave][lane][2 * i + 1] = b.y;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s_sm[wave][lane][i] = sum[i];
+    __syncthreads();
+    // 512 columns per block, 256 threads: two columns each
+    for (int c = threadIdx.x; c < kWave * 8; c += kStatsBlock) {
+        const int l = c >> 3, i = c & 7;
+        float a = s_mn[0][l][i], b = s_mx[0][l][i];
+        double s = s_sm[0][l][i];
+#pragma unroll
+        for (int w = 1; w < kStatsWaves; ++w) {
+            a = fminf(a, s_mn[w][l][i]);
+            b = fmaxf(b, s_mx[w][l][i]);
+            s += s_sm[w][l][i];
+        }
+        const int64_t k = (int64_t)blockIdx.x * kWave * 8 + c;
+        if (k < K) {
+            const int64_t o = (int64_t)blockIdx.y * K + k;
+            pmin[o] = a; pmax[o] = b; psum[o] = s;
+        }
+    }
+}
+
+// ---- binary32: 4 columns per lane, every element added in fp64
+__global__ __launch_bounds__(kStatsBlock) void col_stats_partial_f32(
+    const float* __restrict__ M, int64_t rows, int64_t K, int64_t ld, int64_t rows_per_slice,
+    float* __restrict__ pmin, float* __restrict__ pmax, double* __restrict__ psum)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t col = ((int64_t)blockIdx.x * kWave + lane) * 4;
+    const bool active = col < K;
+    const int64_t r_begin = (int64_t)blockIdx.y * rows_per_slice;
+    const int64_t r_end = min(rows, r_begin + rows_per_slice);
+    float mn[4] = {INFINITY, INFINITY, INFINITY, INFINITY};
+    float mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    double sum[4] = {0, 0, 0, 0};
+    if (active) {
+        const float* base = M + col;
+        int64_t r = r_begin + wave;
+        for (; r + (int64_t)(kRowBatch - 1) * kStatsWaves < r_end; r += (int64_t)kRowBatch * kStatsWaves) {
+            Float4 v[kRowBatch];
+#pragma unroll
+            for (int j = 0; j < kRowBatch; ++j)
+                v[j] = *reinterpret_cast<const Float4*>(base + (r + (int64_t)j * kStatsWaves) * ld);
+#pragma unroll
+            for (int j = 0; j < kRowBatch; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    mn[i] = fminf(mn[i], v[j].f[i]);
+                    mx[i] = fmaxf(mx[i], v[j].f[i]);
+                    sum[i] += (double)v[j].f[i];
+                }
+        }
+        for (; r < r_end; r += kStatsWaves) {
+            Float4 v = *reinterpret_cast<const Float4*>(base + r * ld);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                mn[i] = fminf(mn[i], v.f[i]);
+                mx[i] = fmaxf(mx[i], v.f[i]);
+                sum[i] += (double)v.f[i];
+            }
+        }
+    }
+    __shared__ float s_mn[kStatsWaves][kWave][4];
+    __shared__ float s_mx[kStatsWaves][kWave][4];
+    __shared__ double s_sm[kStatsWaves][kWave][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s_mn[wave][lane][i] = mn[i];
+        s_mx[wave][lane][i] = mx[i];
+        s_sm[wave][lane][i] = sum[i];
+    }
+    __syncthreads();
+    {
+        const int c = threadIdx.x;  // 256 columns per block, one per thread
+        const int l = c >> 2, i = c & 3;
+        float a = s_mn[0][l][i], b = s_mx[0][l][i];
+        double s = s_sm[0][l][i];
+#pragma unroll
+        for (int w = 1; w < kStatsWaves; ++w) {
+            a = fminf(a, s_mn[w][l][i]);
+            b = fmaxf(b, s_mx[w][l][i]);
+            s += s_sm[w][l][i];
+        }
+        const int64_t k = (int64_t)blockIdx.x * kWave * 4 + c;
+        if (k < K) {
+            const int64_t o = (int64_t)blockIdx.y * K + k;
+            pmin[o] = a; pmax[o] = b; psum[o] = s;
+        }
+    }
+}
+
+// Fold the row slices (fixed order) and merge with what the caller already holds.
+__global__ __launch_bounds__(256) void col_stats_merge(
+    const float* __restrict__ pmin, const float* __restrict__ pmax, const double* __restrict__ psum,
+    int slices, int64_t K, int64_t rows, float* __restrict__ cmin, float* __restrict__ cmax,
+    double* __restrict__ csum, uint64_t* __restrict__ count, int accumulate, uint32_t* status)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k == 0 && count) *count = (accumulate ? *count : 0ull) + (uint64_t)rows;
+    if (k >= K) return;
+    float a = INFINITY, b = -INFINITY;
+    double s = 0.0;
+    for (int j = 0; j < slices; ++j) {
+        a = fminf(a, pmin[(int64_t)j * K + k]);
+        b = fmaxf(b, pmax[(int64_t)j * K + k]);
+        s += psum[(int64_t)j * K + k];
+    }
+    // a non-finite input makes the fp64 sum (Inf / NaN) or an extreme (Inf) non-finite
+    if (!isfinite(s) || isinf(a) || isinf(b)) raise_status(status, AWEQ_ST_NONFINITE);
+    if (accumulate) {
+        a = fminf(a, cmin[k]);
+        b = fmaxf(b, cmax[k]);
+        if (csum) s += csum[k];
+    }
+    cmin[k] = a;
+    cmax[k] = b;
+    if (csum) csum[k] = s;
+}
+
+// r = max - min per channel, R = tensor max - tensor min, p = r / R  (Eq. 4).  One block.
+__global__ __launch_bounds__(1024) void col_stats_finalize(
+    const float* __restrict__ cmin, const float* __restrict__ cmax, int64_t K,
+    float* __restrict__ r, float* __restrict__ R, float* __restrict__ p)
+{
+    __shared__ float slot[16];
+    float a = INFINITY, b = -INFINITY;
+    for (int64_t k = threadIdx.x; k < K; k += blockDim.x) {
+        a = fminf(a, cmin[k]);
+        b = fmaxf(b, cmax[k]);
+    }
+    a = block_allreduce<16>(a, OpMin(), slot);
+    b = block_allreduce<16>(b, OpMax(), slot);
+    const float RR = b - a;
+    if (threadIdx.x == 0) *R = RR;
+    for (int64_t k = threadIdx.x; k < K; k += blockDim.x) {
+        const float rk = cmax[k] - cmin[k];
+        r[k] = rk;
+        if (p) p[k] = rk / RR;
+    }
+}
+
+size_t stats_ws_bytes_export(int64_t rows, int64_t K) { return stats_ws_bytes(rows, K); }
+
+}  // namespace aweq
+
+using namespace aweq;
+
+extern "C" int aweq_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int64_t ld,
+                                float* cmin, float* cmax, double* csum, uint64_t* count,
+                                int accumulate, int finalize, float* r, float* R, float* p,
+                                void* ws, size_t ws_bytes, uint32_t* status, void* stream)
+{
+    if (!M || !cmin || !cmax) return AWEQ_ERR_NULL;
+    if (finalize && (!r || !R)) return AWEQ_ERR_NULL;
+    if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
+    if (rows <= 0 || K <= 0 || ld < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
+    const size_t es = dtype_size(dt);
+    if (!aligned16(M) || ((size_t)ld * es) % 16 != 0) return AWEQ_ERR_ALIGN;
+    if (!ws || ws_bytes < stats_ws_bytes(rows, K)) return AWEQ_ERR_WORKSPACE;
+    if (!aligned16(ws)) return AWEQ_ERR_ALIGN;
+
+    hipStream_t st = as_stream(stream);
+    const int epl = dt == AWEQ_F16 ? 8 : 4;
+    const StatsPlan plan = stats_plan(rows, K, epl);
+    // workspace layout: psum (fp64) first, then pmin, pmax
+    double* psum = reinterpret_cast<double*>(ws);
+    float* pmin = reinterpret_cast<float*>(psum + (size_t)plan.slices * K);
+    float* pmax = pmin + (size_t)plan.slices * K;
+    dim3 grid(plan.col_chunks, plan.slices);
+    if (dt == AWEQ_F16)
+        col_stats_partial_f16<<<grid, kStatsBlock, 0, st>>>(reinterpret_cast<const _Float16*>(M), rows, K, ld,
+                                                             plan.rows_per_slice, pmin, pmax, psum);
+    else
+        col_stats_partial_f32<<<grid, kStatsBlock, 0, st>>>(reinterpret_cast<const float*>(M), rows, K, ld,
+                                                             plan.rows_per_slice, pmin, pmax, psum);
+    col_stats_merge<<<(unsigned)cdiv(K, 256), 256, 0, st>>>(pmin, pmax, psum, plan.slices, K, rows, cmin, cmax,
+                                                            csum, count, accumulate, status);
+    if (finalize) col_stats_finalize<<<1, 1024, 0, st>>>(cmin, cmax, K, r, R, p);
+    return launch_status();
+}
