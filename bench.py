@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the AWEQ calibration + quantization hot path on one MI355X.
+
+A step = one pass of the whole path (statistics, equalization, weight quantizer,
+activation quantizer + W8A8 int8 GEMM, bias correction) over every linear layer of one
+decoder block, on synthetic inputs already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--cfg 2] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--cfg", type=int, default=2, help="workload (BASELINE.json configs index + 1); 2 = OPT-6.7B block")
+    ap.add_argument("--tokens", type=int, default=0, help="override the number of calibration tokens (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--out-deq", action="store_true", help="GEMM writes the de-quantised fp16 output instead of int32")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, lin, seed, tokens):
+    """The oracle, as it stands, on a bounded sample of the same workload (host cores)."""
+    import numpy as np
+    from oracle import aweq_oracle as orc
+    from paper_2311_01305_amd import synth
+    X = synth.make_act_np(seed, tokens, lin.K, wl)
+    W = synth.make_weight_np(seed, lin.N, lin.K, wl.dtype)
+    b = synth.make_bias_np(seed, lin.N, wl.has_bias)
+    t0 = time.perf_counter()
+    sx, sw = orc.col_stats(X), orc.col_stats(W, want_sum=False)
+    r_x, _, _ = orc.ranges(sx["cmin"], sx["cmax"])
+    r_w, _, _ = orc.ranges(sw["cmin"], sw["cmax"])
+    s, inv_s, _ = orc.scales(r_x, r_w)
+    Wh = orc.fold_weight(W, s)
+    lo, hi, mu = orc.xhat_stats(sx["cmin"], sx["cmax"], sx["csum"], sx["count"], inv_s)
+    step, zero, _ = orc.qparams(lo, hi, 8)
+    q = orc.quant_weight(Wh, 8, 0)
+    wq = orc.pack_codes(q["codes_u"], 8)
+    a = orc.quant_act(X, inv_s, step, zero)
+    acc = orc.gemm_i8(a["xq"], wq)
+    csa = acc.astype(np.int64).sum(axis=0)
+    orc.bias_w8a8(Wh, mu, tokens, csa, a["colsum_xq"], q["rowsum_w"], step, zero, q["step"], q["zero"], b)
+    dt = time.perf_counter() - t0
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{lin.name} {lin.N}x{lin.K} of cfg {wl.cfg}, {tokens} of {wl.T} calibration tokens, "
+                      f"all stages incl. int8 GEMM, {dt:.2f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus must be 1 (no multi-GPU path exists: the "
+              "calibration path shards over tokens or layers without changing the kernels)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2311_01305_amd import binding as B
+    from paper_2311_01305_amd import pipeline, synth
+
+    B.load_library()  # raises if libaweq.so is missing: no fallback
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.cfg]
+    T = args.tokens or wl.T
+    tdt = torch.float16 if wl.dtype == "f16" else torch.float32
+    dt = B.AWEQ_F16 if wl.dtype == "f16" else B.AWEQ_F32
+
+    layers = []
+    for li, lin in enumerate(wl.linears):
+        seed = synth.layer_seed(wl.cfg, li)
+        X = synth.make_act_torch(seed, T, lin.K, wl, dev)
+        W = synth.make_weight_torch(seed, lin.N, lin.K, wl.dtype, dev)
+        b = synth.make_bias_np(seed, lin.N, wl.has_bias)
+        b = torch.from_numpy(b).to(dev) if b is not None else None
+        buf = pipeline.LayerBuffers(T, lin.K, lin.N, tdt, want_out_i32=not args.out_deq, want_out_deq=args.out_deq,
+                                    device=dev)
+        layers.append((lin, X, W, b, buf))
+    torch.cuda.synchronize()
+
+    stages = ("stats_x", "stats_w", "equalize", "quant_weight", "quant_act", "gemm", "bias")
+
+    def run_layer(lin, X, W, b, buf, ev=None):
+        """The same call sequence as pipeline.calibrate_layer, with the activation quantizer and
+        the GEMM issued as two calls so that each can be bracketed by events."""
+        t = buf.t
+        K, N = lin.K, lin.N
+        st = t["status"]
+
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        B.aweq_calib_stats(X, dt, T, K, K, t["xmin"], t["xmax"], t["xsum"], t["count"], 0, 1, t["r_x"], t["R_x"],
+                           t["p_x"], t["ws"], st)
+        mark(1)
+        B.aweq_calib_stats(W, dt, N, K, K, t["wmin"], t["wmax"], None, t["wcount"], 0, 1, t["r_w"], t["R_w"],
+                           t["p_w"], t["ws"], st)
+        mark(2)
+        B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, 1, t["s"], t["inv_s"], W,
+                        t["W_hat"], dt, N, K, None, t["xhat_range"], t["mu_xhat"], t["act_step"], t["act_zero"], st)
+        mark(3)
+        B.aweq_quant_weight(t["W_hat"], dt, N, K, K, 8, 0, t["codes"], t["step_w"], t["zero_w"], t["rowsum_w"],
+                            t["ws"], st)
+        mark(4)
+        B.aweq_quant_act(X, dt, T, K, K, t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],
+                         t["colsum_xq"], st)
+        mark(5)
+        B.aweq_w8a8_gemm(t["xq"], B.AWEQ_I8, T, K, K, None, t["act_step"], t["act_zero"], None, t["rowsum_x"], None,
+                         t["codes"], N, t["step_w"], t["zero_w"], t["rowsum_w"], b, t.get("out_i32"), t.get("out_deq"),
+                         dt, N, t["colsum_acc"], None, st)
+        mark(6)
+        B.aweq_bias_correct(B.BIAS_W8A8, t["W_hat"], dt, N, K, K, t["mu_xhat"], T, t["colsum_acc"], t["colsum_xq"],
+                            t["rowsum_w"], t["act_step"], t["act_zero"], None, 8, 0, t["step_w"], t["zero_w"], b,
+                            t["delta"], t["bias_out"], 1, None, st)
+        mark(7)
+
+    def step(evs=None):
+        for i, (lin, X, W, b, buf) in enumerate(layers):
+            run_layer(lin, X, W, b, buf, None if evs is None else evs[i])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    all_evs = [[[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in layers] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(all_evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    # per-stage device time from the events (ms, summed over steps)
+    stage_ms = {s: [0.0] * len(layers) for s in stages}
+    for k in range(args.steps):
+        for i in range(len(layers)):
+            for j, s in enumerate(stages):
+                stage_ms[s][i] += all_evs[k][i][j].elapsed_time(all_evs[k][i][j + 1])
+    n_gemm = args.steps * len(layers)
+    gemm_ms_total = sum(stage_ms["gemm"])
+    gemm_ops_total = args.steps * sum(2.0 * T * lin.N * lin.K for lin, *_ in layers)
+    gemm_tops = gemm_ops_total / (gemm_ms_total * 1e-3) / 1e12
+    calib_ms = sum(sum(stage_ms[s]) for s in ("stats_x", "stats_w", "equalize", "quant_weight", "bias"))
+    tokens_per_s = len(layers) * T / (ms_per_step * 1e-3)
+
+    esz = 2 if wl.dtype == "f16" else 4
+    per_layer = []
+    for i, (lin, *_rest) in enumerate(layers):
+        ms = {s: stage_ms[s][i] / args.steps for s in stages}
+        per_layer.append({
+            "name": lin.name, "N": lin.N, "K": lin.K,
+            "ms": {s: round(v, 4) for s, v in ms.items()},
+            "stats_x_GBs": round(T * lin.K * esz / (ms["stats_x"] * 1e-3) / 1e9, 1),
+            "quant_act_GBs": round(T * lin.K * (esz + 1) / (ms["quant_act"] * 1e-3) / 1e9, 1),
+            "gemm_TOPs": round(2.0 * T * lin.N * lin.K / (ms["gemm"] * 1e-3) / 1e12, 1),
+        })
+
+    status_bits = 0
+    for _lin, _X, _W, _b, buf in layers:
+        status_bits |= int(buf.t["status"].item())
+
+    out = {
+        "metric": "calibration tokens/sec per layer (stats+equalize+quant+bias); W8A8 GEMM TOPS",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{wl.cfg} {wl.name}: {len(layers)} linears, T={T} calibration tokens, "
+                               f"{wl.dtype} in, W8 per-channel / A8 per-tensor, "
+                               f"GEMM output {'fp16 de-quantised' if args.out_deq else 'int32'} + column sums",
+                   "value_is": "layers * T / step time, whole path incl. activation quantizer and int8 GEMM"},
+        "calib_tokens_per_s_per_layer_excl_w8a8": T * len(layers) / (calib_ms / args.steps * 1e-3),
+        "gemm_tops": gemm_tops,
+        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": gemm_tops, "peak": INT8_PEAK_TOPS,
+                     "unit": "TFLOP/s", "frac": gemm_tops / INT8_PEAK_TOPS, "traffic": None,
+                     "note": "int8 multiply-add = 2 ops; achieved = sum 2*T*N*K / sum of event-timed GEMM launches "
+                             f"({n_gemm} launches, avg {gemm_ms_total / n_gemm:.3f} ms)"},
+        "layers": per_layer,
+        "status_bits": status_bits,
+    }
+    if not args.no_cpu_baseline:
+        lin0 = wl.linears[0]
+        out["cpu_baseline"] = cpu_baseline(wl, lin0, synth.layer_seed(wl.cfg, 0), min(T, 8192))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
