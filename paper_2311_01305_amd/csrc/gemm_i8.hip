@@ -3,14 +3,23 @@
 // de-quantised output, and the per-output-channel sum over tokens (int64) that feeds the
 // bias correction of Sec. 3.3.
 //
-// MFMA-bound.  One workgroup (4 wavefronts, one per SIMD) owns a 256 x 256 tile of the
-// output; each wavefront owns 128 x 128 of it as 4 x 4 v_mfma_i32_32x32x32_i8 tiles
-// (256 accumulator registers per lane).  Both operands are K-contiguous, so a lane's MFMA
-// operand is 16 consecutive bytes of one row; tiles of 256 rows x 64 bytes are staged in LDS
-// with an XOR swizzle of the 16-byte chunks and double-buffered against the global loads.
+// MFMA-bound.  Two kernels:
+//  - gemm_i8_fast (K % 128 == 0, 16-byte aligned outputs): one workgroup of 8 wavefronts
+//    (two per SIMD) owns a 256 x 256 output tile, each wavefront 128 (t) x 64 (n) of it as
+//    4 x 2 v_mfma_i32_32x32x32_i8 tiles.  Both operands are K-contiguous, so a lane's MFMA
+//    operand is 16 consecutive bytes of one row.  Stages of 256 rows x 128 bytes per operand
+//    (full 128-byte cache lines: a 64-byte stage makes the vector L1 fetch every line twice)
+//    are brought in with LDS-DMA loads (global_load_lds_dwordx4, no staging registers), XOR
+//    swizzled by choosing which 16-byte chunk each lane fetches, double-buffered (2 x 64 KiB),
+//    with the loads, the LDS fragment reads for the next quarter stage and the MFMAs
+//    interleaved by hand.  The MFMA is issued with the weight fragment as its first operand, so
+//    a lane ends up with four consecutive n of one token: 16-byte output stores.
+//  - gemm_i8_generic (any K % 16 == 0, any alignment): 4 wavefronts, 64-byte stages through
+//    registers; slower, used for shapes the fast kernel does not take.
 // Workgroups are numbered so that the ones resident on one XCD (which share an L2) form a
 // compact patch of the output.
 #include "common.hpp"
+#include <type_traits>
 
 namespace aweq {
 
@@ -51,7 +60,7 @@ struct GemmArgs {
     int tiles_m, tiles_n, patch_m, patch_n, patches_n, n_patches;
 };
 
-__global__ __launch_bounds__(kGemmThreads) void gemm_i8_kernel(GemmArgs g)
+__global__ __launch_bounds__(kGemmThreads) void gemm_i8_generic(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     // [buffer][A | B][kTileBytes]
@@ -243,6 +252,298 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_i8_kernel(GemmArgs g)
     }
 }
 
+
+// ---------------------------------------------------------------------------- fast kernel
+namespace fast {
+constexpr int kThreads = 512;
+constexpr int FBK = 128;
+constexpr int kTile = BM * FBK;      // 32 KiB per operand
+constexpr int kStage = 2 * kTile;    // 64 KiB
+constexpr int kLds = 2 * kStage;     // 128 KiB
+
+// chunk swizzle for 128-byte tile rows: rows sharing LDS banks get distinct chunk positions
+// both for 8 and for 16 consecutive rows read at one chunk index
+__device__ __forceinline__ int g8(int r) { return (((r >> 1) & 3) << 1) | (((r >> 3) ^ r) & 1); }
+
+// LDS-DMA load the compiler does not track (it would otherwise wait for every outstanding one
+// before each LDS read): lane i's 16 bytes land at lds_addr + 16 i, lds_addr wave-uniform.
+__device__ __forceinline__ void dma16(const int8_t* gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+
+#define SB() __builtin_amdgcn_sched_barrier(0)
+#define MF(A_, B_, i, j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(B_[j], A_[i], acc[i][j], 0, 0, 0)
+
+// DEQ: 0 none, 1 fp32, 2 fp16
+template <bool I32, int DEQ, bool COLSUM>
+__global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int b = blockIdx.x;
+    const int xcd = b % kXcds, seq = b / kXcds;
+    const int per_patch = g.patch_m * g.patch_n;
+    const int patch = (seq / per_patch) * kXcds + xcd;
+    if (patch >= g.n_patches) return;
+    const int within = seq % per_patch;
+    const int pm = patch / g.patches_n, pn = patch % g.patches_n;
+    const int tile_m = pm * g.patch_m + within % g.patch_m;
+    const int tile_n = pn * g.patch_n + within / g.patch_m;
+    if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+
+    // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 8 rows x 128 B
+    // per instruction; lane i sits at row i / 8, chunk slot i % 8 and fetches chunk slot ^ g8(row)
+    const int lrow = lane >> 3, lslot = lane & 7;
+    const int8_t* ga[4];
+    const int8_t* gb[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = wave * 32 + q * 8 + lrow;
+        const int chunk = lslot ^ g8(row);
+        // rows past the edge re-read the last valid row; their results are never stored
+        const int64_t ra = min(m0 + row, g.T - 1), rb = min(n0 + row, g.N - 1);
+        ga[q] = g.A + ra * g.K + chunk * 16;
+        gb[q] = g.B + rb * g.K + chunk * 16;
+    }
+    const int ns = (int)(g.K / FBK);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const uint32_t wave_off = __builtin_amdgcn_readfirstlane(wave) * 4096;
+
+    v16i acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    // fragment of quarter qq: lane reads row lane % 32 of a 32-row sub-tile, chunk 2 qq + lane / 32
+    const int fr_row = lane & 31, fr_half = lane >> 5;
+    const int fsw = g8(fr_row);
+    int offA[4], offB[4];
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq) {
+        offA[qq] = (wm * 128 + fr_row) * FBK + ((qq * 2 + fr_half) ^ fsw) * 16;
+        offB[qq] = kTile + (wn * 64 + fr_row) * FBK + ((qq * 2 + fr_half) ^ fsw) * 16;
+    }
+    v4i a0[4], b0[2], a1[4], b1[2];
+
+#define RDA(dst, qq, i) dst[i] = *reinterpret_cast<const v4i*>(st + offA[qq] + (i) * 32 * FBK)
+#define RDB(dst, qq, j) dst[j] = *reinterpret_cast<const v4i*>(st + offB[qq] + (j) * 32 * FBK)
+#define DMA_A(q) dma16(ga[q] + kload, dst_stage + (q) * 1024)
+#define DMA_B(q) dma16(gb[q] + kload, dst_stage + kTile + (q) * 1024)
+
+    {
+        const uint32_t dst_stage = lds0 + wave_off;
+        const int64_t kload = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { DMA_A(q); DMA_B(q); }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    {
+        const char* st = lds;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) RDA(a0, 0, i);
+        RDB(b0, 0, 0); RDB(b0, 0, 1);
+    }
+
+    // one stage (128 bytes of K) = four quarters of 8 MFMAs per wave.  F0 / F1 are the two
+    // fragment register sets; each quarter multiplies one and fetches the other.
+    auto stage = [&](int s, auto has_next_c) {
+        constexpr bool NEXT = decltype(has_next_c)::value;
+        const char* st = lds + (s & 1) * kStage;
+        const uint32_t dst_stage = lds0 + ((s + 1) & 1) * kStage + wave_off;
+        const int64_t kload = (int64_t)(s + 1) * FBK;
+        // quarter 0: multiply F0, fetch F1 = quarter 1; the other buffer is free (every wave
+        // passed the barrier of the previous stage), so the next stage starts loading
+        SB();
+        RDA(a1, 1, 0); RDB(b1, 1, 0); RDB(b1, 1, 1); MF(a0, b0, 0, 0);
+        SB();
+        RDA(a1, 1, 1); RDA(a1, 1, 2); MF(a0, b0, 0, 1);
+        SB();
+        RDA(a1, 1, 3); MF(a0, b0, 1, 0);
+        SB();
+        if constexpr (NEXT) DMA_A(0);
+        MF(a0, b0, 1, 1);
+        SB();
+        if constexpr (NEXT) DMA_A(1);
+        MF(a0, b0, 2, 0); MF(a0, b0, 2, 1);
+        SB();
+        if constexpr (NEXT) DMA_A(2);
+        MF(a0, b0, 3, 0);
+        SB();
+        if constexpr (NEXT) DMA_A(3);
+        MF(a0, b0, 3, 1);
+        SB();
+        // quarter 1: multiply F1, fetch F0 = quarter 2
+        RDA(a0, 2, 0); RDB(b0, 2, 0); RDB(b0, 2, 1); MF(a1, b1, 0, 0);
+        SB();
+        RDA(a0, 2, 1); RDA(a0, 2, 2); MF(a1, b1, 0, 1);
+        SB();
+        RDA(a0, 2, 3); MF(a1, b1, 1, 0);
+        SB();
+        if constexpr (NEXT) DMA_B(0);
+        MF(a1, b1, 1, 1);
+        SB();
+        if constexpr (NEXT) DMA_B(1);
+        MF(a1, b1, 2, 0); MF(a1, b1, 2, 1);
+        SB();
+        if constexpr (NEXT) DMA_B(2);
+        MF(a1, b1, 3, 0);
+        SB();
+        if constexpr (NEXT) DMA_B(3);
+        MF(a1, b1, 3, 1);
+        SB();
+        // quarter 2: multiply F0, fetch F1 = quarter 3
+        RDA(a1, 3, 0); RDB(b1, 3, 0); RDB(b1, 3, 1); MF(a0, b0, 0, 0);
+        SB();
+        RDA(a1, 3, 1); RDA(a1, 3, 2); MF(a0, b0, 0, 1);
+        SB();
+        RDA(a1, 3, 3); MF(a0, b0, 1, 0);
+        SB();
+        MF(a0, b0, 1, 1); MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
+        SB();
+        if constexpr (NEXT) {
+            // my loads of the next stage have landed, my reads of this stage are done; after the
+            // barrier that holds for every wave
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            SB();
+            st = lds + ((s + 1) & 1) * kStage;
+            // quarter 3: multiply F1, fetch F0 = quarter 0 of the next stage
+            RDA(a0, 0, 0); RDB(b0, 0, 0); RDB(b0, 0, 1); MF(a1, b1, 0, 0);
+            SB();
+            RDA(a0, 0, 1); RDA(a0, 0, 2); MF(a1, b1, 0, 1);
+            SB();
+            RDA(a0, 0, 3); MF(a1, b1, 1, 0);
+            SB();
+            MF(a1, b1, 1, 1); MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+            SB();
+        } else {
+            MF(a1, b1, 0, 0); MF(a1, b1, 0, 1); MF(a1, b1, 1, 0); MF(a1, b1, 1, 1);
+            MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+        }
+    };
+    int s = 0;
+    for (; s + 1 < ns; ++s) stage(s, std::true_type{});
+    stage(s, std::false_type{});
+#undef RDA
+#undef RDB
+#undef DMA_A
+#undef DMA_B
+
+    // ---- epilogue.  With the weight fragment as first MFMA operand, register v of lane l in
+    // sub-tile (i, j) is token t = m0 + 128 wm + 32 i + l % 32 and output channel
+    // n = n0 + 64 wn + 32 j + 8 (v / 4) + 4 (l / 32) + v % 4: four consecutive n per register quad.
+    // Each wave turns its 32 (t) x 64 (n) slab of sub-tile row i around in a private LDS region
+    // (row pitch 272 bytes: conflict-free both ways) so that a lane then holds 16 bytes of one
+    // output row and 16 lanes cover 256 contiguous bytes: whole cache lines per store.
+    constexpr int kPitch = 64 * 4 + 16;
+    __syncthreads();  // every wave is done with the stage buffers
+    char* slab = lds + wave * (32 * kPitch);
+    const int wr_off = (lane & 31) * kPitch + (lane >> 5) * 16;  // + (32 j + 8 q) * 4
+    const int rd_r = lane >> 4, rd_c = lane & 15;
+    const int rd_off = rd_r * kPitch + rd_c * 16;                // + 4 p * kPitch
+    const int64_t n = n0 + wn * 64 + rd_c * 4;                   // this lane's four channels
+    const bool n_ok = n < g.N;                                   // N % 4 == 0: all four or none
+    const int64_t t_wave = m0 + wm * 128 + rd_r;
+
+    // per-channel constants of the de-quantisation
+    double scale[4] = {0, 0, 0, 0}, bsd[4] = {0, 0, 0, 0};
+    unsigned cn[4] = {0, 0, 0, 0}, zw[4] = {0, 0, 0, 0};
+    if constexpr (DEQ != 0) {
+        if (n_ok) {
+            const int zx = *g.act_zero - 128;
+            const double sx = (double)*g.act_step;
+            const Float4 sw = *reinterpret_cast<const Float4*>(g.step_w + n);
+            const v4i zw4 = *reinterpret_cast<const v4i*>(g.zero_w + n);
+            const v4i rw4 = *reinterpret_cast<const v4i*>(g.rowsum_w + n);
+            Float4 bs = {{0.f, 0.f, 0.f, 0.f}};
+            if (g.bias) bs = *reinterpret_cast<const Float4*>(g.bias + n);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                zw[c] = (unsigned)(zw4[c] - 128);
+                scale[c] = sx * (double)sw.f[c];
+                bsd[c] = (double)bs.f[c];
+                // integer part in wrap-around 32-bit arithmetic: the final value fits (|.| <= 255^2 K)
+                cn[c] = (unsigned)g.K * (unsigned)zx * zw[c] - (unsigned)zx * (unsigned)rw4[c];
+            }
+        }
+    }
+    long long csum[4] = {0, 0, 0, 0};
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v4i o = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                *reinterpret_cast<v4i*>(slab + wr_off + (32 * j + 8 * q) * 4) = o;
+            }
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const v4i o = *reinterpret_cast<const v4i*>(slab + rd_off + 4 * p * kPitch);
+            const int64_t t = t_wave + i * 32 + 4 * p;
+            if (t < g.T && n_ok) {
+                if constexpr (I32) __builtin_nontemporal_store(o, reinterpret_cast<v4i*>(g.out_i32 + t * g.ldo + n));
+                if constexpr (DEQ != 0) {
+                    const unsigned rsx = (unsigned)g.rowsum_x[t];
+                    float y[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const unsigned iv = (unsigned)o[c] + cn[c] - zw[c] * rsx;
+                        y[c] = (float)((double)(int)iv * scale[c] + bsd[c]);
+                    }
+                    if constexpr (DEQ == 2) {
+                        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                        h4 oh = {(_Float16)y[0], (_Float16)y[1], (_Float16)y[2], (_Float16)y[3]};
+                        __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out_deq) + t * g.ldo + n));
+                    } else {
+                        typedef float f4 __attribute__((ext_vector_type(4)));
+                        f4 of = {y[0], y[1], y[2], y[3]};
+                        __builtin_nontemporal_store(of, reinterpret_cast<f4*>(reinterpret_cast<float*>(g.out_deq) + t * g.ldo + n));
+                    }
+                }
+                if constexpr (COLSUM) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) csum[c] += o[c];
+                }
+            }
+        }
+    }
+
+    if constexpr (COLSUM) {
+        // lanes l, l ^ 16, l ^ 32 hold the same channels for different tokens; then the two
+        // waves stacked along t meet in LDS and one of them adds to the global sums
+        long long* tot = reinterpret_cast<long long*>(lds + 8 * 32 * kPitch);  // [wn][64]
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            csum[c] += partner<4>(csum[c]);
+            csum[c] += partner<5>(csum[c]);
+        }
+        if (wm == 1 && lane < 16) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) tot[wn * 64 + lane * 4 + c] = csum[c];
+        }
+        __syncthreads();
+        if (wm == 0 && lane < 16 && n_ok) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                atomicAdd(reinterpret_cast<unsigned long long*>(&g.colsum_acc[n + c]),
+                          (unsigned long long)(csum[c] + tot[wn * 64 + lane * 4 + c]));
+        }
+    }
+}
+#undef SB
+#undef MF
+}  // namespace fast
+
 __global__ void zero_fill_u32_gemm(uint32_t* p, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -320,10 +621,30 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
 
     if (colsum_acc) zero_fill_u32_gemm<<<(unsigned)cdiv(2 * N, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_acc), 2 * N);
+
+    // the fast kernel wants whole 128-byte stages and 16-byte output quads
+    bool fast_ok = (K % fast::FBK) == 0 && (N % 4) == 0;
+    if (out_i32 && (!aligned16(out_i32) || (ldo % 4) != 0)) fast_ok = false;
+    if (out_deq && (!aligned16(out_deq) || (ldo % 4) != 0 || !aligned16(step_w) || !aligned16(zero_w) ||
+                    !aligned16(rowsum_w) || (bias && !aligned16(bias))))
+        fast_ok = false;
+    if (fast_ok) {
+        const int deq = out_deq ? (out_dt == AWEQ_F16 ? 2 : 1) : 0;
+        const void* fn = nullptr;
+#define AWEQ_PICK(I, D, C) if ((out_i32 != nullptr) == I && deq == D && (colsum_acc != nullptr) == C) fn = reinterpret_cast<const void*>(fast::gemm_i8_fast<I, D, C>);
+        AWEQ_PICK(true, 0, true) AWEQ_PICK(true, 0, false) AWEQ_PICK(false, 0, true)
+        AWEQ_PICK(true, 1, true) AWEQ_PICK(true, 1, false) AWEQ_PICK(false, 1, true) AWEQ_PICK(false, 1, false)
+        AWEQ_PICK(true, 2, true) AWEQ_PICK(true, 2, false) AWEQ_PICK(false, 2, true) AWEQ_PICK(false, 2, false)
+#undef AWEQ_PICK
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, fast::kLds) != hipSuccess) return AWEQ_ERR_LAUNCH;
+        void* args[] = {&g};
+        if (hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(fast::kThreads), args, fast::kLds, st) != hipSuccess) return AWEQ_ERR_LAUNCH;
+        return launch_status();
+    }
     const size_t lds_bytes = 2 * 2 * kTileBytes;  // 64 KiB
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_generic), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds_bytes) != hipSuccess)
         return AWEQ_ERR_LAUNCH;
-    gemm_i8_kernel<<<(unsigned)blocks, kGemmThreads, lds_bytes, st>>>(g);
+    gemm_i8_generic<<<(unsigned)blocks, kGemmThreads, lds_bytes, st>>>(g);
     return launch_status();
 }

@@ -358,7 +358,11 @@ def gpu_gemm(B, xq, wq, want_i32=True, deq=None, colsum=True):
     (1000, 700, 1040),   # K not a multiple of the k-step (K % 64 = 16)
     (2048, 1024, 4096),
     (1, 1, 16),
-    (700, 2100, 128),    # more than one patch along N
+    (700, 2100, 128),    # more than one patch along N; one 128-byte stage
+    (1000, 700, 1024),   # K % 128 == 0: LDS-DMA kernel, ragged in both directions
+    (515, 1028, 384),    # LDS-DMA kernel, three stages, ragged
+    (256, 256, 256),
+    (300, 202, 256),     # N % 4 != 0: falls back to the generic kernel
 ])
 def test_gemm_parity(B, orc, T, N, K):
     progress(f"gemm T={T} N={N} K={K}")
@@ -375,17 +379,19 @@ def test_gemm_parity(B, orc, T, N, K):
     assert np.array_equal(host(cs2), host(cs))
 
 
+@pytest.mark.parametrize("K", [320, 384])   # generic kernel / LDS-DMA kernel
 @pytest.mark.parametrize("odt", [np.float32, np.float16])
-def test_gemm_dequant_epilogue(B, orc, odt):
-    progress(f"gemm dequant epilogue {odt.__name__}")
+def test_gemm_dequant_epilogue(B, orc, odt, K):
+    progress(f"gemm dequant epilogue {odt.__name__} K={K}")
     rng = np.random.default_rng(3)
-    T, N, K = 300, 260, 320
+    T, N = 300, 260
     xq = rng.integers(-128, 128, (T, K), dtype=np.int8)
     wq = rng.integers(-128, 128, (N, K), dtype=np.int8)
     deq = dict(dtype=odt, step_x=0.0123, zero_x=141, step_w=rng.uniform(1e-4, 1e-3, N).astype(np.float32),
                zero_w=rng.integers(90, 170, N).astype(np.int32), bias=rng.standard_normal(N).astype(np.float32),
                rowsum_x=xq.astype(np.int64).sum(axis=1).astype(np.int32), rowsum_w=wq.astype(np.int64).sum(axis=1).astype(np.int32))
-    _, out_deq, _ = gpu_gemm(B, xq, wq, deq=deq)
+    _, out_deq, cs = gpu_gemm(B, xq, wq, deq=deq)
+    assert np.array_equal(host(cs), orc.gemm_i8(xq, wq).astype(np.int64).sum(axis=0))
     ref = orc.w8a8_output_direct(xq, wq, deq["step_x"], deq["zero_x"], deq["step_w"], deq["zero_w"], deq["bias"])
     got = host(out_deq).astype(np.float64)
     if odt == np.float32:
