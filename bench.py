@@ -30,6 +30,9 @@ def parse():
     ap.add_argument("--tokens", type=int, default=0, help="override the number of calibration tokens (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-deq", action="store_true", help="GEMM writes the de-quantised fp16 output instead of int32")
+    ap.add_argument("--layers", default="", help="comma-separated layer names to keep (profiling runs)")
+    ap.add_argument("--copy-probe", type=int, default=0,
+                    help="only run a plain device copy of this many bytes (reference for the HBM counters) and exit")
     return ap.parse_args()
 
 
@@ -77,13 +80,33 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        # a plain copy kernel of known size: what FETCH_SIZE / WRITE_SIZE read for it gives the
+        # factor that turns those counters into bytes
+        src = torch.empty(args.copy_probe, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        print(json.dumps({"copy_probe_bytes": args.copy_probe, "ms": ms,
+                          "GBs_read_plus_write": 2 * args.copy_probe / ms / 1e6}))
+        return
     wl = synth.WORKLOADS[args.cfg]
     T = args.tokens or wl.T
     tdt = torch.float16 if wl.dtype == "f16" else torch.float32
     dt = B.AWEQ_F16 if wl.dtype == "f16" else B.AWEQ_F32
 
     layers = []
+    keep = set(x for x in args.layers.split(",") if x)
     for li, lin in enumerate(wl.linears):
+        if keep and lin.name not in keep:
+            continue
         seed = synth.layer_seed(wl.cfg, li)
         X = synth.make_act_torch(seed, T, lin.K, wl, dev)
         W = synth.make_weight_torch(seed, lin.N, lin.K, wl.dtype, dev)

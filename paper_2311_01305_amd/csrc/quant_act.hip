@@ -13,6 +13,7 @@
 // smaller whenever beta <= 1 - 2^-20.  Steps with a significand above that, exponents
 // outside [-60, 60], zero points beyond 2^23 and binary32 inputs take the true division.
 #include "common.hpp"
+#include <type_traits>
 
 namespace aweq {
 
@@ -45,45 +46,47 @@ __device__ __forceinline__ ActParams act_params(const float* act_step, const int
     return p;
 }
 
-// stored code q = clamp(round(a / Step) + Z, 0, 255) - 128 for one value
+// One unit (8 consecutive columns of one row): codes, packed store, column / row sums.
+// FAST: the division-free quotient; the unsigned code is kept as an (integral) float, packed
+// with v_cvt_pk_u8_f32 and turned into the stored signed code by flipping the top bit
+// (u - 128 = u ^ 0x80 as a byte).  Column sums accumulate u in fp32 (exact: at most 512 rows
+// of values <= 255 per block); the caller subtracts 128 per row afterwards.
 template <bool FAST>
-__device__ __forceinline__ int act_code(float a, const ActParams& p, float& big, uint32_t& st)
-{
-    if constexpr (FAST) {
-        float q = a * p.rstep;
-        float r = __builtin_fmaf(-p.step, q, a);
-        q = __builtin_fmaf(r, p.rstep, q);
-        r = __builtin_fmaf(-p.step, q, a);
-        q = __builtin_fmaf(r, p.rstep, q);
-        const float n = rintf(q);
-        big = fmaxf(big, fabsf(n));
-        // |Z| < 2^23: the clamp can be taken on the (integral) float before the conversion
-        return (int)__builtin_amdgcn_fmed3f(n, p.lo_f, p.hi_f) + p.zoff;
-    } else {
-        return quant_div(a, p.step, p.zero, 255, st) - 128;
-    }
-}
-
-template <bool F16, bool FAST>
 __device__ __forceinline__ void act_unit(const float x[8], const float is[8], const ActParams& p, int8_t* dst,
-                                         int cs[8], int& rs, float& big, uint32_t& st)
+                                         float csf[8], int csi[8], int& rs, float& big, uint32_t& st)
 {
-    int c[8];
+    uint32_t w[2] = {0u, 0u};
+    if constexpr (FAST) {
+        const float zf = (float)p.zero;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float a = x[i] * is[i];
-        c[i] = act_code<FAST>(a, p, big, st);
-        cs[i] += c[i];
-    }
-    uint32_t w0 = 0, w1 = 0;
+        for (int i = 0; i < 8; ++i) {
+            const float a = x[i] * is[i];
+            float q = a * p.rstep;
+            float r = __builtin_fmaf(-p.step, q, a);
+            q = __builtin_fmaf(r, p.rstep, q);
+            r = __builtin_fmaf(-p.step, q, a);
+            q = __builtin_fmaf(r, p.rstep, q);
+            const float n = rintf(q);
+            big = fmaxf(big, fabsf(n));
+            // |Z| < 2^23: n + Z is exact wherever it can land inside [0, 255]
+            const float u = __builtin_amdgcn_fmed3f(n + zf, 0.0f, 255.0f);
+            csf[i] += u;
+            w[i >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(u, i & 3, w[i >> 2]);
+        }
+        w[0] ^= 0x80808080u;
+        w[1] ^= 0x80808080u;
+    } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        w0 |= (uint32_t)(c[i] & 0xff) << (8 * i);
-        w1 |= (uint32_t)(c[4 + i] & 0xff) << (8 * i);
+        for (int i = 0; i < 8; ++i) {
+            const float a = x[i] * is[i];
+            const int c = quant_div(a, p.step, p.zero, 255, st) - 128;
+            csi[i] += c;
+            w[i >> 2] |= (uint32_t)(c & 0xff) << (8 * (i & 3));
+        }
     }
-    rs = __builtin_amdgcn_sdot4((int)w0, 0x01010101, rs, false);
-    rs = __builtin_amdgcn_sdot4((int)w1, 0x01010101, rs, false);
-    *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
+    rs = __builtin_amdgcn_sdot4((int)w[0], 0x01010101, rs, false);
+    rs = __builtin_amdgcn_sdot4((int)w[1], 0x01010101, rs, false);
+    *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
 }
 
 template <bool F16>
@@ -126,8 +129,7 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     int64_t col[kQaVpt];
     bool valid[kQaVpt];
     float is[kQaVpt][8];
-    int cs[kQaVpt][8];
-    bool fast = p.fast;
+    bool fast_thread = p.fast;
 #pragma unroll
     for (int j = 0; j < kQaVpt; ++j) {
         col[j] = col0 + ((int64_t)threadIdx.x + j * kQaBlock) * 8;
@@ -135,43 +137,52 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             is[j][i] = valid[j] ? inv_s[col[j] + i] : 1.0f;
-            cs[j][i] = 0;
             // the exactness argument needs a y not to overflow: binary16 |x| < 2^16, Step >= 2^-60
-            if (!(fabsf(is[j][i]) < 1.0e12f)) fast = false;
+            if (!(fabsf(is[j][i]) < 1.0e12f)) fast_thread = false;
         }
     }
+    // one path for the whole block (the choice is uniform unless an inv_s is absurd)
+    const bool fast = __syncthreads_and(fast_thread ? 1 : 0) != 0;
     uint32_t st = 0;
     float big = 0.0f;
+    float csf[kQaVpt][8];
+    int csi[kQaVpt][8];
+#pragma unroll
+    for (int j = 0; j < kQaVpt; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { csf[j][i] = 0.0f; csi[j][i] = 0; }
 
-    for (int rb = 0; rb < nrows; rb += kQaRowBatch) {
-        float x[kQaRowBatch][kQaVpt][8];
+    auto rows_loop = [&](auto fast_c) {
+        constexpr bool FAST = decltype(fast_c)::value;
+        for (int rb = 0; rb < nrows; rb += kQaRowBatch) {
+            float x[kQaRowBatch][kQaVpt][8];
 #pragma unroll
-        for (int b = 0; b < kQaRowBatch; ++b)
+            for (int b = 0; b < kQaRowBatch; ++b)
 #pragma unroll
-            for (int j = 0; j < kQaVpt; ++j)
-                if (rb + b < nrows && valid[j]) load_unit8<F16>(X, (r0 + rb + b) * ldx + col[j], x[b][j]);
+                for (int j = 0; j < kQaVpt; ++j)
+                    if (rb + b < nrows && valid[j]) load_unit8<F16>(X, (r0 + rb + b) * ldx + col[j], x[b][j]);
 #pragma unroll
-        for (int b = 0; b < kQaRowBatch; ++b) {
-            if (rb + b >= nrows) break;
-            int rs = 0;
+            for (int b = 0; b < kQaRowBatch; ++b) {
+                if (rb + b >= nrows) break;
+                int rs = 0;
 #pragma unroll
-            for (int j = 0; j < kQaVpt; ++j)
-                if (valid[j]) {
-                    int8_t* dst = xq + (r0 + rb + b) * K + col[j];
-                    if (fast) act_unit<F16, true>(x[b][j], is[j], p, dst, cs[j], rs, big, st);
-                    else act_unit<F16, false>(x[b][j], is[j], p, dst, cs[j], rs, big, st);
-                }
-            rs = wave_allreduce(rs, OpAdd());
-            if (lane == 0) lds_rs[rb + b][wave] = rs;
+                for (int j = 0; j < kQaVpt; ++j)
+                    if (valid[j]) act_unit<FAST>(x[b][j], is[j], p, xq + (r0 + rb + b) * K + col[j], csf[j], csi[j], rs, big, st);
+                rs = wave_allreduce(rs, OpAdd());
+                if (lane == 0) lds_rs[rb + b][wave] = rs;
+            }
         }
-    }
+    };
+    if (fast) rows_loop(std::true_type{});
+    else rows_loop(std::false_type{});
     if (big >= 16777216.0f) st |= AWEQ_ST_BIGQUOT;
     raise_status(status, st);
 
 #pragma unroll
     for (int j = 0; j < kQaVpt; ++j)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) lds_cs[(threadIdx.x + j * kQaBlock) * 8 + i] = cs[j][i];
+        for (int i = 0; i < 8; ++i)
+            lds_cs[(threadIdx.x + j * kQaBlock) * 8 + i] = fast ? ((int)csf[j][i] - 128 * nrows) : csi[j][i];
     __syncthreads();
     if (rowsum_x)
         for (int i = threadIdx.x; i < nrows; i += kQaBlock) {

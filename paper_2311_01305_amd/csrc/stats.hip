@@ -199,21 +199,36 @@ __global__ __launch_bounds__(kStatsBlock) void col_stats_partial_f32(
     }
 }
 
-// Fold the row slices (fixed order) and merge with what the caller already holds.
-__global__ __launch_bounds__(256) void col_stats_merge(
+// Fold the row slices and merge with what the caller already holds.  A block owns 32 columns;
+// its 8 groups of 32 threads take every 8th slice each and meet in LDS in a fixed order, so
+// the fp64 sums are reproducible.
+constexpr int kMergeCols = 32, kMergeParts = 8;
+__global__ __launch_bounds__(kMergeCols * kMergeParts) void col_stats_merge(
     const float* __restrict__ pmin, const float* __restrict__ pmax, const double* __restrict__ psum,
     int slices, int64_t K, int64_t rows, float* __restrict__ cmin, float* __restrict__ cmax,
     double* __restrict__ csum, uint64_t* __restrict__ count, int accumulate, uint32_t* status)
 {
-    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (k == 0 && count) *count = (accumulate ? *count : 0ull) + (uint64_t)rows;
-    if (k >= K) return;
+    __shared__ float s_a[kMergeParts][kMergeCols], s_b[kMergeParts][kMergeCols];
+    __shared__ double s_s[kMergeParts][kMergeCols];
+    const int c = threadIdx.x & (kMergeCols - 1), part = threadIdx.x / kMergeCols;
+    const int64_t k = (int64_t)blockIdx.x * kMergeCols + c;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && count) *count = (accumulate ? *count : 0ull) + (uint64_t)rows;
     float a = INFINITY, b = -INFINITY;
     double s = 0.0;
-    for (int j = 0; j < slices; ++j) {
-        a = fminf(a, pmin[(int64_t)j * K + k]);
-        b = fmaxf(b, pmax[(int64_t)j * K + k]);
-        s += psum[(int64_t)j * K + k];
+    if (k < K)
+        for (int j = part; j < slices; j += kMergeParts) {
+            a = fminf(a, pmin[(int64_t)j * K + k]);
+            b = fmaxf(b, pmax[(int64_t)j * K + k]);
+            s += psum[(int64_t)j * K + k];
+        }
+    s_a[part][c] = a; s_b[part][c] = b; s_s[part][c] = s;
+    __syncthreads();
+    if (part != 0 || k >= K) return;
+#pragma unroll
+    for (int q = 1; q < kMergeParts; ++q) {
+        a = fminf(a, s_a[q][c]);
+        b = fmaxf(b, s_b[q][c]);
+        s += s_s[q][c];
     }
     // a non-finite input makes the fp64 sum (Inf / NaN) or an extreme (Inf) non-finite
     if (!isfinite(s) || isinf(a) || isinf(b)) raise_status(status, AWEQ_ST_NONFINITE);
@@ -283,7 +298,7 @@ extern "C" int aweq_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int6
     else
         col_stats_partial_f32<<<grid, kStatsBlock, 0, st>>>(reinterpret_cast<const float*>(M), rows, K, ld,
                                                              plan.rows_per_slice, pmin, pmax, psum);
-    col_stats_merge<<<(unsigned)cdiv(K, 256), 256, 0, st>>>(pmin, pmax, psum, plan.slices, K, rows, cmin, cmax,
+    col_stats_merge<<<(unsigned)cdiv(K, kMergeCols), kMergeCols * kMergeParts, 0, st>>>(pmin, pmax, psum, plan.slices, K, rows, cmin, cmax,
                                                             csum, count, accumulate, status);
     if (finalize) col_stats_finalize<<<1, 1024, 0, st>>>(cmin, cmax, K, r, R, p);
     return launch_status();
