@@ -20,6 +20,15 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 
+# HBM bytes per GEMM launch, measured with `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
+# on this workload (profiles/gemm_i8_fast_opt6.7b_hbm_traffic.txt), scaled by what the same
+# counters read for a plain 1 GiB device copy (FETCH x2.0, WRITE x1.0).  Keyed by (N, K), T = 262144.
+GEMM_TRAFFIC_BYTES = {
+    (4096, 4096): (6.46e9, 4.44e9),
+    (16384, 4096): (25.8e9, 17.8e9),
+    (4096, 16384): (25.8e9, 4.45e9),
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -196,6 +205,11 @@ def main():
             "gemm_TOPs": round(2.0 * T * lin.N * lin.K / (ms["gemm"] * 1e-3) / 1e12, 1),
         })
 
+    traffic = None
+    if T == 262144 and all((lin.N, lin.K) in GEMM_TRAFFIC_BYTES for lin, *_ in layers):
+        traffic = sum(sum(GEMM_TRAFFIC_BYTES[(lin.N, lin.K)]) for lin, *_ in layers) / len(layers) / 1e9
+    algorithmic_gb = sum(T * lin.K + lin.N * lin.K + 4.0 * T * lin.N for lin, *_ in layers) / len(layers) / 1e9
+
     status_bits = 0
     for _lin, _X, _W, _b, buf in layers:
         status_bits |= int(buf.t["status"].item())
@@ -220,9 +234,11 @@ def main():
         "calib_tokens_per_s_per_layer_excl_w8a8": T * len(layers) / (calib_ms / args.steps * 1e-3),
         "gemm_tops": gemm_tops,
         "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel", "achieved": gemm_tops, "peak": INT8_PEAK_TOPS,
-                     "unit": "TFLOP/s", "frac": gemm_tops / INT8_PEAK_TOPS, "traffic": None,
-                     "note": "int8 multiply-add = 2 ops; achieved = sum 2*T*N*K / sum of event-timed GEMM launches "
-                             f"({n_gemm} launches, avg {gemm_ms_total / n_gemm:.3f} ms)"},
+                     "unit": "TFLOP/s", "frac": gemm_tops / INT8_PEAK_TOPS, "traffic": traffic,
+                     "traffic_unit": "GB of HBM traffic per launch (fetch + write, mean over the layer shapes; "
+                                     f"algorithmic {algorithmic_gb:.1f} GB: operands once + int32 output)",
+                     "note": "int8 multiply-add = 2 ops (TOP/s); achieved = sum 2*T*N*K / sum of event-timed GEMM "
+                             f"launches ({n_gemm} launches, avg {gemm_ms_total / n_gemm:.3f} ms)"},
         "layers": per_layer,
         "status_bits": status_bits,
     }
