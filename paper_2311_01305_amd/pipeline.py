@@ -103,3 +103,82 @@ def calibrate_layer(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tenso
                             t["codes"], buf.bits, buf.group, t["step_w"], t["zero_w"], bias, t["delta"],
                             t["bias_out"], enable_bc, None, st, stream)
     return t
+
+
+@dataclass
+class GroupBuffers:
+    """Buffers of a group of linears that read the same activation (q/k/v, gate/up): one
+    statistics pass, one equalization scale (from the merged weight ranges), one activation
+    quantization; per linear its folded weight, codes, GEMM output sums and bias."""
+    T: int
+    K: int
+    Ns: tuple
+    dtype: torch.dtype
+    want_out_i32: bool = False
+    want_out_deq: bool = False
+    device: str = "cuda:0"
+    t: dict = field(default_factory=dict)
+    per: list = field(default_factory=list)
+
+    def __post_init__(self):
+        d, T, K = self.device, self.T, self.K
+        f32, i32, i64, f64 = torch.float32, torch.int32, torch.int64, torch.float64
+        e = lambda *shape, dtype: torch.empty(shape, dtype=dtype, device=d)
+        t = self.t
+        for name in ("xmin", "xmax", "wmin", "wmax", "r_x", "p_x", "r_w", "p_w", "s", "inv_s", "mu_xhat"):
+            t[name] = e(K, dtype=f32)
+        t["xsum"] = e(K, dtype=f64)
+        t["count"], t["wcount"] = e(1, dtype=i64), e(1, dtype=i64)
+        t["R_x"], t["R_w"] = e(1, dtype=f32), e(1, dtype=f32)
+        t["xhat_range"] = e(2, dtype=f32)
+        t["act_step"], t["act_zero"] = e(1, dtype=f32), e(1, dtype=i32)
+        t["status"] = torch.zeros(1, dtype=i32, device=d)
+        t["xq"] = e(T, K, dtype=torch.int8)
+        t["rowsum_x"] = e(T, dtype=i32)
+        t["colsum_xq"] = e(K, dtype=i64)
+        ws = max([B.aweq_workspace_size(B.OP_CALIB_STATS, T, K, 0)] +
+                 [B.aweq_workspace_size(B.OP_CALIB_STATS, N, K, N) for N in self.Ns] + [16])
+        t["ws"] = e(ws, dtype=torch.uint8)
+        for N in self.Ns:
+            p = {"W_hat": e(N, K, dtype=self.dtype), "codes": e(N, K, dtype=torch.int8), "step_w": e(N, dtype=f32),
+                 "zero_w": e(N, dtype=i32), "rowsum_w": e(N, dtype=i32), "colsum_acc": e(N, dtype=i64),
+                 "delta": e(N, dtype=f32), "bias_out": e(N, dtype=f32)}
+            if self.want_out_i32:
+                p["out_i32"] = e(T, N, dtype=i32)
+            if self.want_out_deq:
+                p["out_deq"] = e(T, N, dtype=self.dtype)
+            self.per.append(p)
+
+
+def calibrate_group(X: torch.Tensor, Ws, biases, gb: GroupBuffers, enable_awe: bool = True, enable_bc: bool = True,
+                    stream=None):
+    """W8A8 calibration of linears sharing the input X (Sec. 3.1: equalization sits at the
+    entrance of the attention block and of the MLP, so layers with a common input share s)."""
+    t, T, K = gb.t, gb.T, gb.K
+    dt = _dt(X)
+    st = t["status"]
+    B.aweq_calib_stats(X, dt, T, K, X.stride(0), t["xmin"], t["xmax"], t["xsum"], t["count"], 0, 1,
+                       t["r_x"], t["R_x"], t["p_x"], t["ws"], st, stream)
+    # weight ranges of the group: min of mins / max of maxes over all its weights
+    for i, W in enumerate(Ws):
+        last = i == len(Ws) - 1
+        B.aweq_calib_stats(W, dt, W.shape[0], K, W.stride(0), t["wmin"], t["wmax"], None, t["wcount"], int(i > 0),
+                           int(last), t["r_w"], t["R_w"], t["p_w"], t["ws"], st, stream)
+    for W, p in zip(Ws, gb.per):
+        N = W.shape[0]
+        B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, enable_awe, t["s"], t["inv_s"],
+                        W, p["W_hat"], dt, N, W.stride(0), None, t["xhat_range"], t["mu_xhat"], t["act_step"],
+                        t["act_zero"], st, stream)
+        B.aweq_quant_weight(p["W_hat"], dt, N, K, K, 8, 0, p["codes"], p["step_w"], p["zero_w"], p["rowsum_w"],
+                            t["ws"], st, stream)
+    B.aweq_quant_act(X, dt, T, K, X.stride(0), t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],
+                     t["colsum_xq"], st, stream)
+    for W, b, p in zip(Ws, biases, gb.per):
+        N = W.shape[0]
+        B.aweq_w8a8_gemm(t["xq"], B.AWEQ_I8, T, K, K, None, t["act_step"], t["act_zero"], None, t["rowsum_x"], None,
+                         p["codes"], N, p["step_w"], p["zero_w"], p["rowsum_w"], b, p.get("out_i32"),
+                         p.get("out_deq"), dt, N, p["colsum_acc"], None, st, stream)
+        B.aweq_bias_correct(B.BIAS_W8A8, p["W_hat"], dt, N, K, K, t["mu_xhat"], T, p["colsum_acc"], t["colsum_xq"],
+                            p["rowsum_w"], t["act_step"], t["act_zero"], None, 8, 0, p["step_w"], p["zero_w"], b,
+                            p["delta"], p["bias_out"], enable_bc, None, st, stream)
+    return gb
