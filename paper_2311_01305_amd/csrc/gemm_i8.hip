@@ -267,9 +267,10 @@ __device__ __forceinline__ int g8(int r) { return (((r >> 1) & 3) << 1) | (((r >
 
 // LDS-DMA load the compiler does not track (it would otherwise wait for every outstanding one
 // before each LDS read): lane i's 16 bytes land at lds_addr + 16 i, lds_addr wave-uniform.
-__device__ __forceinline__ void dma16(const int8_t* gptr, uint32_t lds_addr)
+// The global address is a wave-uniform base (SGPR pair) plus a 32-bit per-lane offset.
+__device__ __forceinline__ void dma16(const int8_t* sbase, uint32_t voff, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
 }
 
 #define SB() __builtin_amdgcn_sched_barrier(0)
@@ -297,16 +298,17 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
     // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 8 rows x 128 B
     // per instruction; lane i sits at row i / 8, chunk slot i % 8 and fetches chunk slot ^ g8(row)
     const int lrow = lane >> 3, lslot = lane & 7;
-    const int8_t* ga[4];
-    const int8_t* gb[4];
+    const int8_t* baseA = g.A + m0 * g.K;
+    const int8_t* baseB = g.B + n0 * g.K;
+    uint32_t oa[4], ob[4];  // byte offsets from the tile's first row: < 256 * K <= 2^23
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int row = wave * 32 + q * 8 + lrow;
         const int chunk = lslot ^ g8(row);
         // rows past the edge re-read the last valid row; their results are never stored
-        const int64_t ra = min(m0 + row, g.T - 1), rb = min(n0 + row, g.N - 1);
-        ga[q] = g.A + ra * g.K + chunk * 16;
-        gb[q] = g.B + rb * g.K + chunk * 16;
+        const int64_t ra = min(m0 + row, g.T - 1) - m0, rb = min(n0 + row, g.N - 1) - n0;
+        oa[q] = (uint32_t)(ra * g.K + chunk * 16);
+        ob[q] = (uint32_t)(rb * g.K + chunk * 16);
     }
     const int ns = (int)(g.K / FBK);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
@@ -333,8 +335,8 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
 
 #define RDA(dst, qq, i) dst[i] = *reinterpret_cast<const v4i*>(st + offA[qq] + (i) * 32 * FBK)
 #define RDB(dst, qq, j) dst[j] = *reinterpret_cast<const v4i*>(st + offB[qq] + (j) * 32 * FBK)
-#define DMA_A(q) dma16(ga[q] + kload, dst_stage + (q) * 1024)
-#define DMA_B(q) dma16(gb[q] + kload, dst_stage + kTile + (q) * 1024)
+#define DMA_A(q) dma16(baseA + kload, oa[q], dst_stage + (q) * 1024)
+#define DMA_B(q) dma16(baseB + kload, ob[q], dst_stage + kTile + (q) * 1024)
 
     {
         const uint32_t dst_stage = lds0 + wave_off;
