@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-deq", action="store_true", help="GEMM writes the de-quantised fp16 output instead of int32")
     ap.add_argument("--layers", default="", help="comma-separated layer names to keep (profiling runs)")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="only measure the sustained shader clock / MFMA rate for three kinds of operand data and exit")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="only run a plain device copy of this many bytes (reference for the HBM counters) and exit")
     return ap.parse_args()
@@ -73,6 +75,20 @@ def cpu_baseline(wl, lin, seed, tokens):
                       f"all stages incl. int8 GEMM, {dt:.2f} s"}
 
 
+def mfma_probe(torch, B, dev, iters=20000, reps=12):
+    """Sustained shader clock and int8 MFMA rate with no memory traffic, per kind of operand data."""
+    out = torch.zeros(3, dtype=torch.int64, device=dev)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    res = {}
+    for mode, name in ((0, "constant_bytes"), (1, "random_bytes"), (2, "small_signed_codes")):
+        for _ in range(reps):  # the clock settles over a few tens of milliseconds
+            B.aweq_probe_mfma_clock(iters, mode, out)
+        cyc, ticks = int(out[0].item()), int(out[1].item())
+        res[name] = {"shader_clock_GHz": cyc / ticks * 0.1, "cycles_per_mfma": cyc / (16.0 * iters),
+                     "TOPs": cus * 4 * 16.0 * iters * 65536 / (ticks * 1e-8) / 1e12}
+    return {"mfma_probe": res, "compute_units": cus}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -89,6 +105,9 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.mfma_probe:
+        print(json.dumps(mfma_probe(torch, B, dev)))
+        return
     if args.copy_probe:
         # a plain copy kernel of known size: what FETCH_SIZE / WRITE_SIZE read for it gives the
         # factor that turns those counters into bytes

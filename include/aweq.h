@@ -168,6 +168,15 @@ int aweq_bias_correct(int mode, const void* W_hat, aweq_dtype dt, int64_t N, int
                       const float* bias_in, float* delta, float* bias_out, int enable_bc,
                       void* ws, size_t ws_bytes, uint32_t* status, void* stream);
 
+/* ---- Diagnostic (not a stage of the method; for measurement reports).  One workgroup of four
+ * wavefronts per compute unit issues iters x 16 back-to-back independent int8 32x32x32 MFMAs with
+ * operand registers holding constant bytes (operand_mode 0), uniformly random bytes (1) or small
+ * signed codes (2), and no memory traffic.  out[3] (device, uint64): shader-clock cycles of one
+ * wavefront's loop, 100 MHz reference ticks of the same interval, a checksum.  The sustained
+ * shader clock under matrix load is out[0] / out[1] x 100 MHz; the MFMA rate is
+ * CUs x 4 x 16 x iters x 65536 ops over out[1] x 10 ns. */
+int aweq_probe_mfma_clock(int iters, int operand_mode, uint64_t* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

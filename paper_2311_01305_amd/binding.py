@@ -18,7 +18,7 @@ BIAS_W8A8, BIAS_WEIGHT_ONLY = 0, 1
 ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD = 1, 2, 4, 8
 
 EXPORTS = ("aweq_workspace_size", "aweq_status_string", "aweq_calib_stats", "aweq_equalize",
-           "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct")
+           "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock")
 
 _vp, _i64, _i32, _u64, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_float, C.c_size_t
 
@@ -59,6 +59,8 @@ def load_library():
     lib.aweq_bias_correct.restype = _i32
     lib.aweq_bias_correct.argtypes = [_i32, _vp, _i32, _i64, _i64, _i64, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
+    lib.aweq_probe_mfma_clock.restype = _i32
+    lib.aweq_probe_mfma_clock.argtypes = [_i32, _i32, _vp, _vp]
     _lib = lib
     return lib
 
@@ -144,3 +146,7 @@ def aweq_bias_correct(mode, W_hat, dt, N, K, ldw, mu_xhat, count, colsum_acc, co
         _ptr(rowsum_w), _ptr(act_step), _ptr(act_zero), _ptr(codes), int(bits), int(group), _ptr(step_w),
         _ptr(zero_w), _ptr(bias_in), _ptr(delta), _ptr(bias_out), int(enable_bc), _ptr(ws),
         _nbytes(ws) if ws_bytes is None else ws_bytes, _ptr(status), _stream(stream)))
+
+
+def aweq_probe_mfma_clock(iters, operand_mode, out, stream=None):
+    _check(load_library().aweq_probe_mfma_clock(int(iters), int(operand_mode), _ptr(out), _stream(stream)))
