@@ -70,6 +70,19 @@ size_t aweq_workspace_size(aweq_op op, int64_t rows, int64_t K, int64_t N);
 /* Name of an AWEQ_ERR_* code.  Host function. */
 const char* aweq_status_string(int code);
 
+/* ---- K-panel layout of the int8 GEMM operands (a storage format of this library, chosen so
+ * that the matrix-core kernel of stage 4 reads whole cache lines: not part of the method).
+ * An int8 matrix M[rows x K] is cut along K into ceil(K / 64) panels of 64 columns; panel p
+ * stores bytes M[r][64 p .. 64 p + 63] of every row r back to back:
+ *     byte offset of M[r][k] = ((k / 64) * rows + r) * 64 + k % 64,
+ * columns past K in the last panel are zero.  xq (stage 4a / 4) and the 8-bit codes of stage 3
+ * with group <= 0 use it.  aweq_panel_bytes: size of such a buffer (host function).
+ * aweq_pack_panels_i8 / aweq_unpack_panels_i8 convert from / to a row-major [rows x K] int8
+ * matrix of pitch ld bytes (K % 8 == 0, ld % 8 == 0, both pointers 8-byte aligned). */
+size_t aweq_panel_bytes(int64_t rows, int64_t K);
+int aweq_pack_panels_i8(const int8_t* src, int64_t rows, int64_t K, int64_t ld, int8_t* panels, void* stream);
+int aweq_unpack_panels_i8(const int8_t* panels, int64_t rows, int64_t K, int8_t* dst, int64_t ld, void* stream);
+
 /* ---- Stage 1: range statistics (Sec. 3.2: channel range = channel max - channel min,
  * tensor range = max - min over all channels, Eq. 4 p_i = r_i / R; Sec. 3.3: E[x] is
  * collected in the same pass).
@@ -111,8 +124,9 @@ int aweq_equalize(const float* xmin, const float* xmax, const double* xsum, uint
  * group = g > 0 (a power of two in [8, 512] dividing K): one per g consecutive k inside a
  *   row -> step/zero[N x K/g];
  * group = -1: one for the whole tensor -> step[1], zero[1] (needs workspace).
- * codes: bits 8 -> int8 u - 128, N*K bytes; bits 4 -> two codes per byte, even k in the
- * low nibble, N*K/2 bytes; bits 3 -> per row a little-endian bit stream with code k in bits
+ * codes: bits 8 -> int8 u - 128; for group <= 0 in the K-panel layout (aweq_panel_bytes(N, K)
+ * bytes: the weight operand of stage 4), for group > 0 row-major, N*K bytes; bits 4 -> two
+ * codes per byte, even k in the low nibble, N*K/2 bytes; bits 3 -> per row a little-endian bit stream with code k in bits
  * [3k, 3k+3), N*3K/8 bytes (K % 32 == 0).  rowsum_w[N] = sum_k (u - 128), bits 8 only,
  * nullable. */
 int aweq_quant_weight(const void* W_hat, aweq_dtype dt, int64_t N, int64_t K, int64_t ldw,
@@ -124,6 +138,7 @@ int aweq_quant_weight(const void* W_hat, aweq_dtype dt, int64_t N, int64_t K, in
  * quantizer (Eq. 1 with b = 8) applied to X_hat = X * inv_s on the fly:
  * xq[t,k] = clamp(round((X[t,k] * inv_s[k]) / Step_x) + Z_x, 0, 255) - 128,
  * rowsum_x[T] = sum_k xq (int32, nullable), colsum_xq[K] = sum_t xq (int64, nullable).
+ * xq is written in the K-panel layout (aweq_panel_bytes(T, K) bytes).
  * act_step / act_zero are the device scalars aweq_equalize wrote. */
 int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx,
                    const float* inv_s, const float* act_step, const int32_t* act_zero,
@@ -132,8 +147,9 @@ int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t l
 
 /* ---- Stage 4: W8A8 forward (Sec. 1-2: INT8 weights and activations).
  * x_dt F16 / F32: X is quantised into xq[T x K] first (stage 4a; xq, inv_s, act_step,
- * act_zero required).  x_dt I8: X already holds xq, stage 4a is skipped.
- * acc[t,n] = sum_k xq[t,k] wq[n,k], int8 x int8 -> int32 on the matrix cores.
+ * act_zero required).  x_dt I8: X already holds xq in the K-panel layout (ldx = K), stage 4a
+ * is skipped.  wq[N x K]: the 8-bit codes of stage 3 (group <= 0), K-panel layout.
+ * acc[t,n] = sum_k xq[t,k] wq[n,k], int8 x int8 -> int32 on the matrix cores (K <= 32768).
  * Outputs, each nullable: out_i32[T x N] (pitch ldo) the raw accumulator;
  * out_deq[T x N] (F16 or F32, pitch ldo) the de-quantised output
  *   Step_x Step_w[n] (acc - Z'x rowsum_w[n] - Z'w[n] rowsum_x[t] + K Z'x Z'w[n]) + bias[n],

@@ -18,7 +18,8 @@ BIAS_W8A8, BIAS_WEIGHT_ONLY = 0, 1
 ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD = 1, 2, 4, 8
 
 EXPORTS = ("aweq_workspace_size", "aweq_status_string", "aweq_calib_stats", "aweq_equalize",
-           "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock")
+           "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock",
+           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8")
 
 _vp, _i64, _i32, _u64, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_float, C.c_size_t
 
@@ -61,6 +62,12 @@ def load_library():
                                       _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
     lib.aweq_probe_mfma_clock.restype = _i32
     lib.aweq_probe_mfma_clock.argtypes = [_i32, _i32, _vp, _vp]
+    lib.aweq_panel_bytes.restype = _sz
+    lib.aweq_panel_bytes.argtypes = [_i64, _i64]
+    lib.aweq_pack_panels_i8.restype = _i32
+    lib.aweq_pack_panels_i8.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp]
+    lib.aweq_unpack_panels_i8.restype = _i32
+    lib.aweq_unpack_panels_i8.argtypes = [_vp, _i64, _i64, _vp, _i64, _vp]
     _lib = lib
     return lib
 
@@ -150,3 +157,15 @@ def aweq_bias_correct(mode, W_hat, dt, N, K, ldw, mu_xhat, count, colsum_acc, co
 
 def aweq_probe_mfma_clock(iters, operand_mode, out, stream=None):
     _check(load_library().aweq_probe_mfma_clock(int(iters), int(operand_mode), _ptr(out), _stream(stream)))
+
+
+def aweq_panel_bytes(rows, K):
+    return int(load_library().aweq_panel_bytes(int(rows), int(K)))
+
+
+def aweq_pack_panels_i8(src, rows, K, ld, panels, stream=None):
+    _check(load_library().aweq_pack_panels_i8(_ptr(src), rows, K, ld, _ptr(panels), _stream(stream)))
+
+
+def aweq_unpack_panels_i8(panels, rows, K, dst, ld, stream=None):
+    _check(load_library().aweq_unpack_panels_i8(_ptr(panels), rows, K, _ptr(dst), ld, _stream(stream)))

@@ -92,7 +92,9 @@ __global__ __launch_bounds__(kBiasBlock) void bias_wonly_kernel(
         load_w8<F16>(row, u, w);
         int c[8];
         if constexpr (BITS == 8) {
-            const uint2 v = *reinterpret_cast<const uint2*>(crow + u * 8);
+            // per-row / per-tensor 8-bit codes are stored in the GEMM's K-panel layout
+            const uint2 v = group > 0 ? *reinterpret_cast<const uint2*>(crow + u * 8)
+                                      : *reinterpret_cast<const uint2*>(codes + ((u >> 3) * (int64_t)gridDim.x + n) * kPanel + (u & 7) * 8);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 c[i] = (int)(int8_t)((v.x >> (8 * i)) & 0xff) + 128;

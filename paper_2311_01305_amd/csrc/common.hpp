@@ -16,6 +16,15 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? AWEQ_OK : AWEQ_ERR_LAUNCH; }
 inline size_t dtype_size(aweq_dtype dt) { return dt == AWEQ_F32 ? 4 : (dt == AWEQ_F16 ? 2 : 1); }
 
+// K-panel layout of an int8 matrix [rows x K] (the GEMM operands): panel p holds bytes
+// 64 p .. 64 p + 63 of every row, rows back to back; columns past K in the last panel are 0.
+constexpr int kPanel = 64;
+__host__ __device__ inline int64_t panel_count(int64_t K) { return (K + kPanel - 1) / kPanel; }
+__host__ __device__ inline int64_t panel_offset(int64_t rows, int64_t r, int64_t k)
+{
+    return ((k / kPanel) * rows + r) * kPanel + (k % kPanel);
+}
+
 // ---------------------------------------------------------------- wavefront primitives
 // Butterfly exchanges over the 64-lane wavefront.  Distances 1..8 are DPP modifiers that
 // stay inside a row of 16 lanes, distance 16 is a ds_swizzle (no LDS traffic), distance 32
@@ -43,6 +52,11 @@ __device__ __forceinline__ int partner_bits(int v)
         return (threadIdx.x & 32) ? (int)r[0] : (int)r[1];
     }
 }
+
+// value of lane l ^ 8 with no assumption about lower levels (row_ror:8 inside a row of 16)
+__device__ __forceinline__ int xor8_bits(int v) { return dpp_mov<0x128>(v); }
+__device__ __forceinline__ float xor8(float v) { return __int_as_float(xor8_bits(__float_as_int(v))); }
+__device__ __forceinline__ int xor8(int v) { return xor8_bits(v); }
 
 template <int LVL>
 __device__ __forceinline__ float partner(float v)

@@ -3,19 +3,25 @@
 // de-quantised output, and the per-output-channel sum over tokens (int64) that feeds the
 // bias correction of Sec. 3.3.
 //
-// MFMA-bound.  Two kernels:
-//  - gemm_i8_fast (K % 128 == 0, 16-byte aligned outputs): one workgroup of 8 wavefronts
+// Both operands arrive in the K-panel layout (64-byte panels of K, rows back to back inside a
+// panel, zero fill past K): the 256 rows x 64 bytes an output tile needs of one panel are one
+// contiguous 16 KiB block, every cache line is used whole, and any K % 8 == 0 works.
+//
+// MFMA-bound by design, load-round-trip-bound in practice, which fixes the structure.  Two kernels:
+//  - gemm_i8_fast (N % 4 == 0, 16-byte aligned outputs): one workgroup of 8 wavefronts
 //    (two per SIMD) owns a 256 x 256 output tile, each wavefront 128 (t) x 64 (n) of it as
-//    4 x 2 v_mfma_i32_32x32x32_i8 tiles.  Both operands are K-contiguous, so a lane's MFMA
-//    operand is 16 consecutive bytes of one row.  Stages of 256 rows x 128 bytes per operand
-//    (full 128-byte cache lines: a 64-byte stage makes the vector L1 fetch every line twice)
-//    are brought in with LDS-DMA loads (global_load_lds_dwordx4, no staging registers), XOR
-//    swizzled by choosing which 16-byte chunk each lane fetches, double-buffered (2 x 64 KiB),
-//    with the loads, the LDS fragment reads for the next quarter stage and the MFMAs
-//    interleaved by hand.  The MFMA is issued with the weight fragment as its first operand, so
-//    a lane ends up with four consecutive n of one token: 16-byte output stores.
-//  - gemm_i8_generic (any K % 16 == 0, any alignment): 4 wavefronts, 64-byte stages through
-//    registers; slower, used for shapes the fast kernel does not take.
+//    4 x 2 v_mfma_i32_32x32x32_i8 tiles; a lane's MFMA operand is 16 consecutive bytes of one
+//    row.  Half-stages of one panel (256 rows x 64 bytes per operand, 32 KiB) go through a ring
+//    of four LDS slots filled by LDS-DMA loads (global_load_lds_dwordx4, no staging registers),
+//    three half-stages ahead of the one being multiplied: the round trip of a load under
+//    load (about 1.5 us when part of it misses the L2) is longer than the 0.5 - 1 us a stage of
+//    MFMAs lasts, so a two-buffer scheme stalls on every stage whatever the issue order.
+//    The slots are XOR swizzled by choosing which 16-byte chunk each lane fetches; loads, LDS
+//    fragment reads for the next K-step and MFMAs are interleaved by hand.  The MFMA is
+//    issued with the weight fragment as its first operand, so a lane ends up with four
+//    consecutive n of one token: 16-byte output stores.
+//  - gemm_i8_generic (any N, any alignment): 4 wavefronts, half-stages through registers;
+//    slower, used for shapes the fast kernel does not take.
 // Workgroups are numbered so that the ones resident on one XCD (which share an L2) form a
 // compact patch of the output.
 #include "common.hpp"
@@ -42,8 +48,8 @@ __device__ __forceinline__ int swz(int row, int chunk)
 }
 
 struct GemmArgs {
-    const int8_t* A;   // xq [T x K]
-    const int8_t* B;   // wq [N x K]
+    const int8_t* A;   // xq [T x K], K-panel layout
+    const int8_t* B;   // wq [N x K], K-panel layout
     int64_t T, N, K;
     int32_t* out_i32;
     void* out_deq;
@@ -95,20 +101,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_i8_generic(GemmArgs g)
         const int row = ld_row + i * (kGemmThreads / kChunksPerRow);
         // rows past the edge re-read the last valid row; their results are never stored
         const int64_t ra = min(m0 + row, g.T - 1), rb = min(n0 + row, g.N - 1);
-        a_ptr[i] = g.A + ra * g.K + ld_chunk * 16;
-        b_ptr[i] = g.B + rb * g.K + ld_chunk * 16;
+        a_ptr[i] = g.A + ra * kPanel + ld_chunk * 16;
+        b_ptr[i] = g.B + rb * kPanel + ld_chunk * 16;
         lds_off[i] = row * BK + swz(row, ld_chunk) * 16;
     }
     v4i ra[kLoadsPerThread], rb[kLoadsPerThread];
-    const int nk = (int)((g.K + BK - 1) / BK);
+    const int nk = (int)panel_count(g.K);
+    const int64_t panelA = g.T * kPanel, panelB = g.N * kPanel;
 
     auto load_global = [&](int kt) {
-        const int64_t k = (int64_t)kt * BK;
-        const bool ok = k + ld_chunk * 16 < g.K;  // K % 16 == 0: a chunk is all in or all out
+        // the last panel is zero filled past K in both operands
 #pragma unroll
         for (int i = 0; i < kLoadsPerThread; ++i) {
-            ra[i] = ok ? *reinterpret_cast<const v4i*>(a_ptr[i] + k) : v4i{0, 0, 0, 0};
-            rb[i] = ok ? *reinterpret_cast<const v4i*>(b_ptr[i] + k) : v4i{0, 0, 0, 0};
+            ra[i] = *reinterpret_cast<const v4i*>(a_ptr[i] + kt * panelA);
+            rb[i] = *reinterpret_cast<const v4i*>(b_ptr[i] + kt * panelB);
         }
     };
     auto store_lds = [&](int buf) {
@@ -256,14 +262,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_i8_generic(GemmArgs g)
 // ---------------------------------------------------------------------------- fast kernel
 namespace fast {
 constexpr int kThreads = 512;
-constexpr int FBK = 128;
-constexpr int kTile = BM * FBK;      // 32 KiB per operand
-constexpr int kStage = 2 * kTile;    // 64 KiB
-constexpr int kLds = 2 * kStage;     // 128 KiB
+constexpr int kHalf = BM * kPanel;   // 16 KiB per operand per slot
+constexpr int kSlot = 2 * kHalf;     // 32 KiB: one panel of the A tile and of the B tile
+constexpr int kSlots = 4;
+constexpr int kLds = kSlots * kSlot; // 128 KiB
 
-// chunk swizzle for 128-byte tile rows: rows sharing LDS banks get distinct chunk positions
-// both for 8 and for 16 consecutive rows read at one chunk index
-__device__ __forceinline__ int g8(int r) { return (((r >> 1) & 3) << 1) | (((r >> 3) ^ r) & 1); }
+// chunk swizzle for 64-byte slot rows: the four rows r, r + 4, r + 8, r + 12 share LDS banks,
+// so 16 consecutive rows read at one chunk index land on distinct banks
+__device__ __forceinline__ int f4(int r) { return (r >> 2) & 3; }
 
 // LDS-DMA load the compiler does not track (it would otherwise wait for every outstanding one
 // before each LDS read): lane i's 16 bytes land at lds_addr + 16 i, lds_addr wave-uniform.
@@ -271,6 +277,11 @@ __device__ __forceinline__ int g8(int r) { return (((r >> 1) & 3) << 1) | (((r >
 __device__ __forceinline__ void dma16(const int8_t* sbase, uint32_t voff, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 #define SB() __builtin_amdgcn_sched_barrier(0)
@@ -295,24 +306,24 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
     if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
 
-    // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 8 rows x 128 B
-    // per instruction; lane i sits at row i / 8, chunk slot i % 8 and fetches chunk slot ^ g8(row)
-    const int lrow = lane >> 3, lslot = lane & 7;
-    const int8_t* baseA = g.A + m0 * g.K;
-    const int8_t* baseB = g.B + n0 * g.K;
-    uint32_t oa[4], ob[4];  // byte offsets from the tile's first row: < 256 * K <= 2^23
+    // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 16 rows x 64 B
+    // per instruction; lane i sits at row i / 4, chunk slot i % 4 and fetches chunk slot ^ f4(row)
+    uint32_t oa[2], ob[2];  // byte offsets from the tile's first row inside a panel: < 16 KiB
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int row = wave * 32 + q * 8 + lrow;
-        const int chunk = lslot ^ g8(row);
+    for (int q = 0; q < 2; ++q) {
+        const int row = wave * 32 + q * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ f4(row);
         // rows past the edge re-read the last valid row; their results are never stored
         const int64_t ra = min(m0 + row, g.T - 1) - m0, rb = min(n0 + row, g.N - 1) - n0;
-        oa[q] = (uint32_t)(ra * g.K + chunk * 16);
-        ob[q] = (uint32_t)(rb * g.K + chunk * 16);
+        oa[q] = (uint32_t)(ra * kPanel + chunk * 16);
+        ob[q] = (uint32_t)(rb * kPanel + chunk * 16);
     }
-    const int ns = (int)(g.K / FBK);
+    const int8_t* srcA = g.A + m0 * kPanel;   // the tile's rows in the panel being fetched
+    const int8_t* srcB = g.B + n0 * kPanel;
+    const int64_t panelA = g.T * kPanel, panelB = g.N * kPanel;
+    const int nh = (int)panel_count(g.K);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
-    const uint32_t wave_off = __builtin_amdgcn_readfirstlane(wave) * 4096;
+    const uint32_t wave_off = __builtin_amdgcn_readfirstlane(wave) * 2048;
 
     v16i acc[4][2];
 #pragma unroll
@@ -322,29 +333,30 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    // fragment of quarter qq: lane reads row lane % 32 of a 32-row sub-tile, chunk 2 qq + lane / 32
+    // fragment of K-step ks of a panel: lane reads row lane % 32 of a 32-row sub-tile, chunk
+    // 2 ks + lane / 32 (sub-tiles start at multiples of 32 rows, so f4(row) = f4(lane % 32))
     const int fr_row = lane & 31, fr_half = lane >> 5;
-    const int fsw = g8(fr_row);
-    int offA[4], offB[4];
+    int offA[2], offB[2];
 #pragma unroll
-    for (int qq = 0; qq < 4; ++qq) {
-        offA[qq] = (wm * 128 + fr_row) * FBK + ((qq * 2 + fr_half) ^ fsw) * 16;
-        offB[qq] = kTile + (wn * 64 + fr_row) * FBK + ((qq * 2 + fr_half) ^ fsw) * 16;
+    for (int ks = 0; ks < 2; ++ks) {
+        offA[ks] = (wm * 128 + fr_row) * kPanel + ((ks * 2 + fr_half) ^ f4(fr_row)) * 16;
+        offB[ks] = kHalf + (wn * 64 + fr_row) * kPanel + ((ks * 2 + fr_half) ^ f4(fr_row)) * 16;
     }
     v4i a0[4], b0[2], a1[4], b1[2];
 
-#define RDA(dst, qq, i) dst[i] = *reinterpret_cast<const v4i*>(st + offA[qq] + (i) * 32 * FBK)
-#define RDB(dst, qq, j) dst[j] = *reinterpret_cast<const v4i*>(st + offB[qq] + (j) * 32 * FBK)
-#define DMA_A(q) dma16(baseA + kload, oa[q], dst_stage + (q) * 1024)
-#define DMA_B(q) dma16(baseB + kload, ob[q], dst_stage + kTile + (q) * 1024)
+#define RDA(dst, ks, i) dst[i] = *reinterpret_cast<const v4i*>(st + offA[ks] + (i) * 32 * kPanel)
+#define RDB(dst, ks, j) dst[j] = *reinterpret_cast<const v4i*>(st + offB[ks] + (j) * 32 * kPanel)
+#define DMA_A(q) dma16(srcA, oa[q], dst_slot + (q) * 1024)
+#define DMA_B(q) dma16(srcB, ob[q], dst_slot + kHalf + (q) * 1024)
 
-    {
-        const uint32_t dst_stage = lds0 + wave_off;
-        const int64_t kload = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { DMA_A(q); DMA_B(q); }
+    // prologue: up to three panels in flight, the first one landed
+    const int pre = nh < 3 ? nh : 3;
+    for (int h = 0; h < pre; ++h) {
+        const uint32_t dst_slot = lds0 + h * kSlot + wave_off;
+        DMA_A(0); DMA_B(0); DMA_A(1); DMA_B(1);
+        srcA += panelA; srcB += panelB;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (pre >= 3) wait_vm<8>(); else if (pre == 2) wait_vm<4>(); else wait_vm<0>();
     __builtin_amdgcn_s_barrier();
     {
         const char* st = lds;
@@ -353,71 +365,41 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         RDB(b0, 0, 0); RDB(b0, 0, 1);
     }
 
-    // one stage (128 bytes of K) = four quarters of 8 MFMAs per wave.  F0 / F1 are the two
-    // fragment register sets; each quarter multiplies one and fetches the other.
-    auto stage = [&](int s, auto has_next_c) {
-        constexpr bool NEXT = decltype(has_next_c)::value;
-        const char* st = lds + (s & 1) * kStage;
-        const uint32_t dst_stage = lds0 + ((s + 1) & 1) * kStage + wave_off;
-        const int64_t kload = (int64_t)(s + 1) * FBK;
-        // quarter 0: multiply F0, fetch F1 = quarter 1; the other buffer is free (every wave
-        // passed the barrier of the previous stage), so the next stage starts loading
+    // one panel (64 bytes of K) = two K-steps of 8 MFMAs per wave.  F0 / F1 are the two fragment
+    // register sets; each K-step multiplies one and fetches the other.  ISSUE: panel h + 3 is
+    // fetched into the slot panel h - 1 occupied (every wave finished reading it before the
+    // barrier of panel h - 1).  WAITN: loads this wave may leave in flight when panel h + 1 has
+    // to be complete (4 per panel issued after it).
+    auto half = [&](int h, auto issue_c, auto waitn_c, auto next_c) {
+        constexpr bool ISSUE = decltype(issue_c)::value;
+        constexpr int WAITN = decltype(waitn_c)::value;
+        constexpr bool NEXT = decltype(next_c)::value;
+        const char* st = lds + (h & 3) * kSlot;
+        const uint32_t dst_slot = lds0 + ((h + 3) & 3) * kSlot + wave_off;
         SB();
         RDA(a1, 1, 0); RDB(b1, 1, 0); RDB(b1, 1, 1); MF(a0, b0, 0, 0);
         SB();
+        if constexpr (ISSUE) DMA_A(0);
         RDA(a1, 1, 1); RDA(a1, 1, 2); MF(a0, b0, 0, 1);
         SB();
+        if constexpr (ISSUE) DMA_B(0);
         RDA(a1, 1, 3); MF(a0, b0, 1, 0);
         SB();
-        if constexpr (NEXT) DMA_A(0);
+        if constexpr (ISSUE) DMA_A(1);
         MF(a0, b0, 1, 1);
         SB();
-        if constexpr (NEXT) DMA_A(1);
-        MF(a0, b0, 2, 0); MF(a0, b0, 2, 1);
+        if constexpr (ISSUE) DMA_B(1);
+        MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
         SB();
-        if constexpr (NEXT) DMA_A(2);
-        MF(a0, b0, 3, 0);
-        SB();
-        if constexpr (NEXT) DMA_A(3);
-        MF(a0, b0, 3, 1);
-        SB();
-        // quarter 1: multiply F1, fetch F0 = quarter 2
-        RDA(a0, 2, 0); RDB(b0, 2, 0); RDB(b0, 2, 1); MF(a1, b1, 0, 0);
-        SB();
-        RDA(a0, 2, 1); RDA(a0, 2, 2); MF(a1, b1, 0, 1);
-        SB();
-        RDA(a0, 2, 3); MF(a1, b1, 1, 0);
-        SB();
-        if constexpr (NEXT) DMA_B(0);
-        MF(a1, b1, 1, 1);
-        SB();
-        if constexpr (NEXT) DMA_B(1);
-        MF(a1, b1, 2, 0); MF(a1, b1, 2, 1);
-        SB();
-        if constexpr (NEXT) DMA_B(2);
-        MF(a1, b1, 3, 0);
-        SB();
-        if constexpr (NEXT) DMA_B(3);
-        MF(a1, b1, 3, 1);
-        SB();
-        // quarter 2: multiply F0, fetch F1 = quarter 3
-        RDA(a1, 3, 0); RDB(b1, 3, 0); RDB(b1, 3, 1); MF(a0, b0, 0, 0);
-        SB();
-        RDA(a1, 3, 1); RDA(a1, 3, 2); MF(a0, b0, 0, 1);
-        SB();
-        RDA(a1, 3, 3); MF(a0, b0, 1, 0);
-        SB();
-        MF(a0, b0, 1, 1); MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
-        SB();
+        if constexpr (ISSUE) { srcA += panelA; srcB += panelB; }
         if constexpr (NEXT) {
-            // my loads of the next stage have landed, my reads of this stage are done; after the
+            // my loads of the next panel have landed, my reads of this one are done; after the
             // barrier that holds for every wave
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wait_vm<WAITN>();
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
             SB();
-            st = lds + ((s + 1) & 1) * kStage;
-            // quarter 3: multiply F1, fetch F0 = quarter 0 of the next stage
+            st = lds + ((h + 1) & 3) * kSlot;
             RDA(a0, 0, 0); RDB(b0, 0, 0); RDB(b0, 0, 1); MF(a1, b1, 0, 0);
             SB();
             RDA(a0, 0, 1); RDA(a0, 0, 2); MF(a1, b1, 0, 1);
@@ -431,9 +413,14 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
             MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
         }
     };
-    int s = 0;
-    for (; s + 1 < ns; ++s) stage(s, std::true_type{});
-    stage(s, std::false_type{});
+    using I0 = std::integral_constant<int, 0>;
+    using I4 = std::integral_constant<int, 4>;
+    using I8 = std::integral_constant<int, 8>;
+    int h = 0;
+    for (; h + 3 < nh; ++h) half(h, std::true_type{}, I8{}, std::true_type{});
+    if (h + 2 < nh) { half(h, std::false_type{}, I4{}, std::true_type{}); ++h; }
+    if (h + 1 < nh) { half(h, std::false_type{}, I0{}, std::true_type{}); ++h; }
+    half(h, std::false_type{}, I0{}, std::false_type{});
 #undef RDA
 #undef RDB
 #undef DMA_A
@@ -575,7 +562,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     (void)ws; (void)ws_bytes;
     if (!X || !wq) return AWEQ_ERR_NULL;
     if (x_dt != AWEQ_F32 && x_dt != AWEQ_F16 && x_dt != AWEQ_I8) return AWEQ_ERR_DTYPE;
-    if (T <= 0 || N <= 0 || K <= 0 || (K % 16) != 0) return AWEQ_ERR_SHAPE;
+    if (T <= 0 || N <= 0 || K <= 0 || (K % 8) != 0) return AWEQ_ERR_SHAPE;
     if (K > 32768) return AWEQ_ERR_SHAPE;  // keeps 128*128*K and 255*255*K inside int32
     const int8_t* a = nullptr;
     if (x_dt == AWEQ_I8) {
@@ -624,8 +611,8 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
 
     if (colsum_acc) zero_fill_u32_gemm<<<(unsigned)cdiv(2 * N, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_acc), 2 * N);
 
-    // the fast kernel wants whole 128-byte stages and 16-byte output quads
-    bool fast_ok = (K % fast::FBK) == 0 && (N % 4) == 0;
+    // the fast kernel stores 16-byte output quads
+    bool fast_ok = (N % 4) == 0;
     if (out_i32 && (!aligned16(out_i32) || (ldo % 4) != 0)) fast_ok = false;
     if (out_deq && (!aligned16(out_deq) || (ldo % 4) != 0 || !aligned16(step_w) || !aligned16(zero_w) ||
                     !aligned16(rowsum_w) || (bias && !aligned16(bias))))

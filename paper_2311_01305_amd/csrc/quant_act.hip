@@ -19,10 +19,11 @@ namespace aweq {
 
 constexpr int kQaBlock = 256;
 constexpr int kQaWaves = kQaBlock / kWave;
-constexpr int kQaVpt = 2;                               // units (8 columns) per thread per row
-constexpr int kQaChunk = kQaBlock * 8 * kQaVpt;         // 4096 columns per block
+constexpr int kQaVpt = 2;                               // panels (units per thread per row) per wavefront
+constexpr int kQaPanels = kQaWaves * kQaVpt;            // 8 panels = 512 columns per block
 constexpr int kQaMaxRows = 512;                         // rows per block (LDS row-sum slots)
-constexpr int kQaRowBatch = 4;                          // rows in flight per thread
+constexpr int kQaRowBatch = 4;                          // groups of 8 rows in flight per thread
+constexpr int kQaRowsPerIter = 8 * kQaRowBatch;
 
 struct ActParams {
     float step, rstep, lo_f, hi_f;
@@ -89,27 +90,42 @@ __device__ __forceinline__ void act_unit(const float x[8], const float is[8], co
     *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
 }
 
-template <bool F16>
-__device__ __forceinline__ void load_unit8(const void* X, int64_t elt, float x[8])
-{
-    if constexpr (F16) {
-        Half8 v = *reinterpret_cast<const Half8*>(reinterpret_cast<const _Float16*>(X) + elt);
+// 8 consecutive input values of one row as loaded (binary16: one 16-byte quad), converted to
+// fp32 only when they are consumed so that the loads in flight stay cheap in registers
+template <bool F16> struct RawUnit;
+template <> struct RawUnit<true> {
+    Half8 v;
+    __device__ __forceinline__ void load(const void* X, int64_t elt) { v = *reinterpret_cast<const Half8*>(reinterpret_cast<const _Float16*>(X) + elt); }
+    __device__ __forceinline__ void get(float x[8]) const
+    {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float2 f = h2f2(v.h[i]);
             x[2 * i] = f.x;
             x[2 * i + 1] = f.y;
         }
-    } else {
+    }
+};
+template <> struct RawUnit<false> {
+    Float4 a, b;
+    __device__ __forceinline__ void load(const void* X, int64_t elt)
+    {
         const float* p = reinterpret_cast<const float*>(X) + elt;
-        Float4 a = *reinterpret_cast<const Float4*>(p), b = *reinterpret_cast<const Float4*>(p + 4);
+        a = *reinterpret_cast<const Float4*>(p);
+        b = *reinterpret_cast<const Float4*>(p + 4);
+    }
+    __device__ __forceinline__ void get(float x[8]) const
+    {
 #pragma unroll
         for (int i = 0; i < 4; ++i) { x[i] = a.f[i]; x[4 + i] = b.f[i]; }
     }
-}
+};
 
-// grid (column chunks of 4096, row slices); every block owns full 4096-column strips of its
-// rows, the four wavefronts side by side along K.
+// grid (column chunks of 8 panels, row slices).  The codes go out in the K-panel layout the
+// GEMM reads (64-byte panels, rows back to back), so a wavefront works on 8 rows x one panel
+// per instruction: lane = 8 (row % 8) + unit; its load covers 8 whole 128-byte lines of
+// binary16 input and its store 512 contiguous bytes of codes.  Each wavefront owns two
+// panels, so a lane keeps the column sums of its 16 columns over the rows it visits.
 template <bool F16>
 __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     const void* __restrict__ X, int64_t T, int64_t K, int64_t ldx, const float* __restrict__ inv_s,
@@ -118,25 +134,29 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     uint32_t* status)
 {
     __shared__ int lds_rs[kQaMaxRows][kQaWaves];
-    __shared__ int lds_cs[kQaChunk];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int64_t col0 = (int64_t)blockIdx.x * kQaChunk;
+    const int rsub = lane >> 3, c8 = lane & 7;
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
     const int nrows = (int)min((int64_t)rows_per_block, T - r0);
+    const int64_t np = panel_count(K);
     const ActParams p = act_params(act_step, act_zero, F16);
 
-    int64_t col[kQaVpt];
-    bool valid[kQaVpt];
+    const int64_t panel0 = (int64_t)blockIdx.x * kQaPanels + wave * kQaVpt;
+    const int col0 = (int)(panel0 * kPanel) + c8 * 8;                      // K <= 2^31 - 1 columns
+    int8_t* const dst0 = xq + (panel0 * T + r0) * kPanel + c8 * 8;         // this lane's 8 bytes of row r0, panel j = 0
+    const int64_t dst_step = T * kPanel;                                   // to the next panel
+    const char* const src0 = reinterpret_cast<const char*>(X) + (r0 * ldx + col0) * (F16 ? 2 : 4);
+    bool valid[kQaVpt], pad[kQaVpt];
     float is[kQaVpt][8];
     bool fast_thread = p.fast;
 #pragma unroll
     for (int j = 0; j < kQaVpt; ++j) {
-        col[j] = col0 + ((int64_t)threadIdx.x + j * kQaBlock) * 8;
-        valid[j] = col[j] < K;
+        valid[j] = col0 + j * kPanel < K;
+        pad[j] = !valid[j] && panel0 + j < np;  // zero fill of the last panel
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            is[j][i] = valid[j] ? inv_s[col[j] + i] : 1.0f;
+            is[j][i] = valid[j] ? inv_s[col0 + j * kPanel + i] : 1.0f;
             // the exactness argument needs a y not to overflow: binary16 |x| < 2^16, Step >= 2^-60
             if (!(fabsf(is[j][i]) < 1.0e12f)) fast_thread = false;
         }
@@ -151,25 +171,40 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     for (int j = 0; j < kQaVpt; ++j)
 #pragma unroll
         for (int i = 0; i < 8; ++i) { csf[j][i] = 0.0f; csi[j][i] = 0; }
+    int my_rows = 0;
 
     auto rows_loop = [&](auto fast_c) {
         constexpr bool FAST = decltype(fast_c)::value;
-        for (int rb = 0; rb < nrows; rb += kQaRowBatch) {
-            float x[kQaRowBatch][kQaVpt][8];
+        for (int rb = 0; rb < nrows; rb += kQaRowsPerIter) {
+            RawUnit<F16> raw[kQaRowBatch][kQaVpt];
 #pragma unroll
             for (int b = 0; b < kQaRowBatch; ++b)
 #pragma unroll
-                for (int j = 0; j < kQaVpt; ++j)
-                    if (rb + b < nrows && valid[j]) load_unit8<F16>(X, (r0 + rb + b) * ldx + col[j], x[b][j]);
+                for (int j = 0; j < kQaVpt; ++j) {
+                    const int row = rb + 8 * b + rsub;
+                    if (row < nrows && valid[j]) raw[b][j].load(src0, (int64_t)row * ldx + j * kPanel);
+                }
 #pragma unroll
             for (int b = 0; b < kQaRowBatch; ++b) {
-                if (rb + b >= nrows) break;
+                const int row = rb + 8 * b + rsub;
+                const bool row_ok = row < nrows;
                 int rs = 0;
+                if (row_ok) {
+                    ++my_rows;
 #pragma unroll
-                for (int j = 0; j < kQaVpt; ++j)
-                    if (valid[j]) act_unit<FAST>(x[b][j], is[j], p, xq + (r0 + rb + b) * K + col[j], csf[j], csi[j], rs, big, st);
-                rs = wave_allreduce(rs, OpAdd());
-                if (lane == 0) lds_rs[rb + b][wave] = rs;
+                    for (int j = 0; j < kQaVpt; ++j) {
+                        int8_t* d = dst0 + j * dst_step + row * kPanel;
+                        if (valid[j]) {
+                            float x[8];
+                            raw[b][j].get(x);
+                            act_unit<FAST>(x, is[j], p, d, csf[j], csi[j], rs, big, st);
+                        } else if (pad[j]) {
+                            *reinterpret_cast<uint2*>(d) = make_uint2(0u, 0u);
+                        }
+                    }
+                }
+                rs = group_allreduce<3>(rs, OpAdd());  // the 8 lanes of one row
+                if (row_ok && c8 == 0) lds_rs[row][wave] = rs;
             }
         }
     };
@@ -178,11 +213,20 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     if (big >= 16777216.0f) st |= AWEQ_ST_BIGQUOT;
     raise_status(status, st);
 
+    if (colsum_xq) {
+        // lanes l, l ^ 8, l ^ 16, l ^ 32 hold the same columns for different rows
 #pragma unroll
-    for (int j = 0; j < kQaVpt; ++j)
+        for (int j = 0; j < kQaVpt; ++j)
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            lds_cs[(threadIdx.x + j * kQaBlock) * 8 + i] = fast ? ((int)csf[j][i] - 128 * nrows) : csi[j][i];
+            for (int i = 0; i < 8; ++i) {
+                int v = fast ? ((int)csf[j][i] - 128 * my_rows) : csi[j][i];
+                v += xor8(v);
+                v += partner<4>(v);
+                v += partner<5>(v);
+                if (lane < 8 && valid[j])
+                    atomicAdd(reinterpret_cast<unsigned long long*>(&colsum_xq[col0 + j * kPanel + i]), (unsigned long long)(long long)v);
+            }
+    }
     __syncthreads();
     if (rowsum_x)
         for (int i = threadIdx.x; i < nrows; i += kQaBlock) {
@@ -191,11 +235,6 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
             for (int w = 0; w < kQaWaves; ++w) tot += lds_rs[i][w];
             if (multi_chunk) atomicAdd(&rowsum_x[r0 + i], tot);
             else rowsum_x[r0 + i] = tot;
-        }
-    if (colsum_xq)
-        for (int c = threadIdx.x; c < kQaChunk; c += kQaBlock) {
-            const int64_t k = col0 + c;
-            if (k < K) atomicAdd(reinterpret_cast<unsigned long long*>(&colsum_xq[k]), (unsigned long long)(long long)lds_cs[c]);
         }
 }
 
@@ -209,10 +248,10 @@ int launch_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t
                      const float* act_step, const int32_t* act_zero, int8_t* xq, int32_t* rowsum_x,
                      int64_t* colsum_xq, uint32_t* status, hipStream_t st)
 {
-    const int chunks = (int)cdiv(K, kQaChunk);
-    int64_t slices = cdiv(4096, chunks);
+    const int chunks = (int)cdiv(panel_count(K), kQaPanels);
+    int64_t slices = cdiv(8192, chunks);
     int64_t rpb = cdiv(T, slices);
-    rpb = cdiv(rpb, kQaRowBatch) * kQaRowBatch;
+    rpb = cdiv(rpb, kQaRowsPerIter) * kQaRowsPerIter;
     if (rpb > kQaMaxRows) rpb = kQaMaxRows;
     slices = cdiv(T, rpb);
     if (slices > 0x7fffffffll) return AWEQ_ERR_SHAPE;

@@ -56,12 +56,13 @@ __device__ __forceinline__ void minmax8(const float x[8], float& lo, float& hi)
 }
 
 // Quantise one unit and store its codes in the format of `bits`.  `row_codes` points at the
-// start of the row's code bytes, u is the unit index inside the row.  Returns sum (u - 128)
+// start of the row's code bytes, u is the unit index inside the row (bits == 8: the unit sits
+// at row_codes + unit_off, which lets the caller pick the layout).  Returns sum (u - 128)
 // (meaningful for bits == 8).  For bits == 3 all four lanes of a quad must call this with
 // consecutive units (u % 4 == lane % 4).
 template <int BITS>
 __device__ __forceinline__ int quant_store_unit(const float x[8], float step, int zero, uint8_t* row_codes,
-                                                int64_t u, uint32_t& st)
+                                                int64_t u, uint32_t& st, int64_t unit_off = -1)
 {
     constexpr int qmax = (1 << BITS) - 1;
     int c[8];
@@ -76,7 +77,7 @@ __device__ __forceinline__ int quant_store_unit(const float x[8], float step, in
             w1 |= (uint32_t)((c[4 + i] - 128) & 0xff) << (8 * i);
             rs += c[i] + c[4 + i] - 256;
         }
-        *reinterpret_cast<uint2*>(row_codes + u * 8) = make_uint2(w0, w1);
+        *reinterpret_cast<uint2*>(row_codes + (unit_off >= 0 ? unit_off : u * 8)) = make_uint2(w0, w1);
         return rs;
     } else if constexpr (BITS == 4) {
         uint32_t w = 0;
@@ -100,7 +101,8 @@ __device__ __forceinline__ int quant_store_unit(const float x[8], float step, in
     }
 }
 
-// ---- one (Step, Z) per row, or one for the tensor (PER_TENSOR: read from step[0]/zero[0])
+// ---- one (Step, Z) per row, or one for the tensor (PER_TENSOR: read from step[0]/zero[0]).
+// 8-bit codes are the GEMM's weight operand and go out in its K-panel layout.
 template <bool F16, int BITS, bool PER_TENSOR>
 __global__ __launch_bounds__(kQwBlock) void quant_weight_row(
     const void* __restrict__ W, int64_t K, int64_t ldw, uint8_t* __restrict__ codes,
@@ -109,9 +111,10 @@ __global__ __launch_bounds__(kQwBlock) void quant_weight_row(
     __shared__ float slot_f[kQwBlock / kWave];
     __shared__ int slot_i[kQwBlock / kWave];
     const int64_t n = blockIdx.x;
+    const int64_t N = gridDim.x;
     const int64_t units = K / 8;
     const char* row = reinterpret_cast<const char*>(W) + (size_t)n * ldw * (F16 ? 2 : 4);
-    uint8_t* row_codes = codes + (size_t)n * (K * BITS / 8);
+    uint8_t* row_codes = BITS == 8 ? codes + (size_t)n * kPanel : codes + (size_t)n * (K * BITS / 8);
     uint32_t st = 0;
 
     Unit<F16> reg[kQwMaxUnits];
@@ -146,8 +149,14 @@ __global__ __launch_bounds__(kQwBlock) void quant_weight_row(
         if (u < units) {
             float x[8];
             reg[j].get(x);
-            rs += quant_store_unit<BITS>(x, sp, z, row_codes, u, st);
+            // unit u of row n in the panel layout: panel u / 8, bytes 8 (u % 8) ..
+            rs += quant_store_unit<BITS>(x, sp, z, row_codes, u, st, BITS == 8 ? (u >> 3) * N * kPanel + (u & 7) * 8 : -1);
         }
+    }
+    if constexpr (BITS == 8) {
+        // columns past K in the last panel are zero
+        const int64_t u = units + threadIdx.x;
+        if (u < panel_count(K) * 8) *reinterpret_cast<uint2*>(row_codes + (u >> 3) * N * kPanel + (u & 7) * 8) = make_uint2(0u, 0u);
     }
     if (BITS == 8 && rowsum_w) {
         rs = block_allreduce<kQwBlock / kWave>(rs, OpAdd(), slot_i);

@@ -51,7 +51,9 @@ class LayerBuffers:
         t["status"] = torch.zeros(1, dtype=i32, device=d)
         t["W_hat"] = e(N, K, dtype=self.dtype)
         ng = 1 if self.group < 0 else (N if self.group == 0 else N * (K // self.group))
-        t["codes"] = e(N * K * self.bits // 8, dtype=torch.int8)
+        # 8-bit per-row / per-tensor codes are the GEMM operand: K-panel layout
+        panel_w = self.bits == 8 and self.group <= 0
+        t["codes"] = e(B.aweq_panel_bytes(N, K) if panel_w else N * K * self.bits // 8, dtype=torch.int8)
         t["step_w"], t["zero_w"] = e(ng, dtype=f32), e(ng, dtype=i32)
         t["rowsum_w"] = e(N, dtype=i32)
         t["delta"], t["bias_out"] = e(N, dtype=f32), e(N, dtype=f32)
@@ -59,7 +61,7 @@ class LayerBuffers:
                  B.aweq_workspace_size(B.OP_QUANT_WEIGHT, N, K, N), 16)
         t["ws"] = e(ws, dtype=torch.uint8)
         if self.w8a8:
-            t["xq"] = e(T, K, dtype=torch.int8)
+            t["xq"] = e(B.aweq_panel_bytes(T, K), dtype=torch.int8)
             t["rowsum_x"] = e(T, dtype=i32)
             t["colsum_xq"] = e(K, dtype=i64)
             t["colsum_acc"] = e(N, dtype=i64)
@@ -133,14 +135,14 @@ class GroupBuffers:
         t["xhat_range"] = e(2, dtype=f32)
         t["act_step"], t["act_zero"] = e(1, dtype=f32), e(1, dtype=i32)
         t["status"] = torch.zeros(1, dtype=i32, device=d)
-        t["xq"] = e(T, K, dtype=torch.int8)
+        t["xq"] = e(B.aweq_panel_bytes(T, K), dtype=torch.int8)
         t["rowsum_x"] = e(T, dtype=i32)
         t["colsum_xq"] = e(K, dtype=i64)
         ws = max([B.aweq_workspace_size(B.OP_CALIB_STATS, T, K, 0)] +
                  [B.aweq_workspace_size(B.OP_CALIB_STATS, N, K, N) for N in self.Ns] + [16])
         t["ws"] = e(ws, dtype=torch.uint8)
         for N in self.Ns:
-            p = {"W_hat": e(N, K, dtype=self.dtype), "codes": e(N, K, dtype=torch.int8), "step_w": e(N, dtype=f32),
+            p = {"W_hat": e(N, K, dtype=self.dtype), "codes": e(B.aweq_panel_bytes(N, K), dtype=torch.int8), "step_w": e(N, dtype=f32),
                  "zero_w": e(N, dtype=i32), "rowsum_w": e(N, dtype=i32), "colsum_acc": e(N, dtype=i64),
                  "delta": e(N, dtype=f32), "bias_out": e(N, dtype=f32)}
             if self.want_out_i32:

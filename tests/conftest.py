@@ -30,3 +30,25 @@ def orc():
     from oracle import aweq_oracle
     aweq_oracle.lib()
     return aweq_oracle
+
+
+def from_panels(buf, rows, K):
+    """Row-major [rows, K] view of an int8 buffer in the library's K-panel layout (panel p =
+    columns 64 p .. 64 p + 63 of every row, rows back to back); checks the zero fill past K."""
+    import numpy as np
+    kp = -(-K // 64)
+    a = np.asarray(buf).reshape(-1)
+    assert a.size >= kp * rows * 64
+    a = a[:kp * rows * 64].reshape(kp, rows, 64).transpose(1, 0, 2).reshape(rows, kp * 64)
+    assert not a[:, K:].any(), "columns past K must be zero"
+    return np.ascontiguousarray(a[:, :K])
+
+
+def to_panels(mat):
+    """K-panel layout (flat) of a row-major int8 matrix."""
+    import numpy as np
+    rows, K = mat.shape
+    kp = -(-K // 64)
+    padded = np.zeros((rows, kp * 64), dtype=mat.dtype)
+    padded[:, :K] = mat
+    return np.ascontiguousarray(padded.reshape(rows, kp, 64).transpose(1, 0, 2)).reshape(-1)

@@ -4,6 +4,7 @@ scale (from their merged weight ranges) and one activation quantization, against
 composition of oracle functions."""
 import numpy as np
 import pytest
+from conftest import from_panels
 
 torch = pytest.importorskip("torch")
 
@@ -56,13 +57,13 @@ def test_block_with_shared_inputs(orc):
         step, zero, _ = orc.qparams(lo, hi, 8)
         assert h(t["act_step"])[0] == step and int(h(t["act_zero"])[0]) == zero
         a = orc.quant_act(X, gi, step, zero)
-        assert np.array_equal(h(t["xq"]), a["xq"]) and np.array_equal(h(t["colsum_xq"]), a["colsum_xq"])
+        assert np.array_equal(from_panels(h(t["xq"]), T, K), a["xq"]) and np.array_equal(h(t["colsum_xq"]), a["colsum_xq"])
         for W, p, (name, N) in zip(Ws, gb.per, lins):
             Wh = orc.fold_weight(W, gs)
             assert np.array_equal(h(p["W_hat"]).view(np.uint16), Wh.view(np.uint16)), name
             q = orc.quant_weight(Wh, 8, 0)
             wq = orc.pack_codes(q["codes_u"], 8)
-            assert np.array_equal(h(p["codes"]), wq), name
+            assert np.array_equal(from_panels(h(p["codes"]), N, K), wq), name
             acc = orc.gemm_i8(a["xq"], wq)
             assert np.array_equal(h(p["out_i32"]), acc), name
             csa = acc.astype(np.int64).sum(axis=0)

@@ -4,6 +4,7 @@ calibration tokens, against the oracle.  The integer stages are compared with th
 the GPU's own fp32 scales (bit-exact given identical scales); scales to 1e-5."""
 import numpy as np
 import pytest
+from conftest import from_panels
 
 torch = pytest.importorskip("torch")
 
@@ -78,11 +79,11 @@ def test_w8a8_layer_shapes(mods, orc, cfg, li, T):
     assert h(t["act_step"])[0] == step and int(h(t["act_zero"])[0]) == zero
     q = orc.quant_weight(Wh, 8, 0)
     wq = orc.pack_codes(q["codes_u"], 8)
-    assert np.array_equal(h(t["codes"]).reshape(lin.N, lin.K), wq)
+    assert np.array_equal(from_panels(h(t["codes"]), lin.N, lin.K), wq)
     assert np.array_equal(h(t["step_w"]), q["step"]) and np.array_equal(h(t["zero_w"]), q["zero"])
     assert np.array_equal(h(t["rowsum_w"]), q["rowsum_w"])
     a = orc.quant_act(X, gi, step, zero)
-    assert np.array_equal(h(t["xq"]), a["xq"]) and np.array_equal(h(t["rowsum_x"]), a["rowsum_x"])
+    assert np.array_equal(from_panels(h(t["xq"]), T, lin.K), a["xq"]) and np.array_equal(h(t["rowsum_x"]), a["rowsum_x"])
     assert np.array_equal(h(t["colsum_xq"]), a["colsum_xq"])
     acc = orc.gemm_i8(a["xq"], wq)
     assert np.array_equal(h(t["out_i32"]), acc)

@@ -10,6 +10,7 @@ they are checked against the oracle fed the GPU's own fp32 scales.
 """
 import numpy as np
 import pytest
+from conftest import from_panels
 
 torch = pytest.importorskip("torch")
 
@@ -82,7 +83,7 @@ def test_fullsize_weight_quantizer(run, orc):
     assert np.array_equal(h(t["W_hat"]).view(np.uint16), Wh.view(np.uint16))
     q = orc.quant_weight(Wh, 8, 0)
     assert np.array_equal(h(t["step_w"]), q["step"]) and np.array_equal(h(t["zero_w"]), q["zero"])
-    assert np.array_equal(h(t["codes"]).reshape(lin.N, lin.K), orc.pack_codes(q["codes_u"], 8))
+    assert np.array_equal(from_panels(h(t["codes"]), lin.N, lin.K), orc.pack_codes(q["codes_u"], 8))
     assert np.array_equal(h(t["rowsum_w"]), q["rowsum_w"])
     run["q"] = q
 
@@ -98,10 +99,17 @@ def test_fullsize_activation_quantizer(run, orc):
     assert np.array_equal(h(t["rowsum_x"]), a["rowsum_x"])
     assert np.array_equal(h(t["colsum_xq"]), a["colsum_xq"])
     rows = sample_rows(wl.T)
-    assert np.array_equal(h(t["xq"][torch.from_numpy(rows).to(DEV)]), a["xq"][rows])
+    assert np.array_equal(h(xq_rows_dev(t["xq"], wl.T, Xh.shape[1], torch.from_numpy(rows).to(DEV))), a["xq"][rows])
     assert a["xq"].min() == -128 and a["xq"].max() == 127
     run["a_rows"] = (rows, a["xq"][rows].copy())
     run["colsum_xq"] = a["colsum_xq"]
+
+
+def xq_rows_dev(xq, T, K, idx):
+    """Rows idx (a tensor of indices or a slice) of the K-panel buffer xq as a row-major [len, K] tensor."""
+    assert K % 64 == 0
+    v = xq.view(K // 64, T, 64)[:, idx, :]
+    return v.permute(1, 0, 2).reshape(-1, K)
 
 
 def sample_rows(T):
@@ -112,11 +120,11 @@ def sample_rows(T):
 
 def test_fullsize_gemm(run, orc):
     t, wl, lin = run["t"], run["wl"], run["lin"]
-    wq = h(t["codes"]).reshape(lin.N, lin.K)
+    wq = from_panels(h(t["codes"]), lin.N, lin.K)
     rows = sample_rows(wl.T)
     idx = torch.from_numpy(rows).to(DEV)
     progress(f"oracle GEMM on {rows.size} sampled rows")
-    xq_rows = h(t["xq"][idx])
+    xq_rows = h(xq_rows_dev(t["xq"], wl.T, lin.K, idx))
     ref = orc.gemm_i8(xq_rows, wq)
     assert np.array_equal(h(t["out_i32"][idx]), ref)
     # Freivalds: acc v = xq (wq^T v) for random 0/1 vectors, exact in fp64 (all values < 2^53)
@@ -127,7 +135,7 @@ def test_fullsize_gemm(run, orc):
     Vd, Ud = torch.from_numpy(V).to(DEV), torch.from_numpy(U).to(DEV)
     for r0 in range(0, wl.T, 32768):
         lhs = t["out_i32"][r0:r0 + 32768].to(torch.float64) @ Vd
-        rhs = t["xq"][r0:r0 + 32768].to(torch.float64) @ Ud
+        rhs = xq_rows_dev(t["xq"], wl.T, lin.K, slice(r0, r0 + 32768)).to(torch.float64) @ Ud
         assert torch.equal(lhs, rhs), f"Freivalds mismatch in rows {r0}.."
     # sum over tokens of the accumulator = wq . (column sums of xq): exact integers
     colsum_xq = run.get("colsum_xq")

@@ -6,6 +6,7 @@ outputs bit-exact given identical fp32 scales; scales and bias corrections <= 1e
 """
 import numpy as np
 import pytest
+from conftest import from_panels, to_panels
 
 torch = pytest.importorskip("torch")
 
@@ -192,7 +193,8 @@ def test_equalize_switch_and_guards(B, orc):
 def gpu_quant_weight(B, Wh, bits, group, want_rowsum=True):
     N, K = Wh.shape
     ng = 1 if group < 0 else (N if group == 0 else N * (K // group))
-    codes = torch.zeros(N * K * bits // 8, dtype=torch.uint8, device=DEV)
+    panel = bits == 8 and group <= 0  # the GEMM's weight operand: K-panel layout
+    codes = torch.full((B.aweq_panel_bytes(N, K) if panel else N * K * bits // 8,), 0x5a, dtype=torch.uint8, device=DEV)
     step, zero = e(ng, dtype=torch.float32), e(ng, dtype=torch.int32)
     rowsum = e(N, dtype=torch.int32) if (bits == 8 and group <= 0 and want_rowsum) else None
     ws = e(64, dtype=torch.uint8)
@@ -231,7 +233,10 @@ def test_quant_weight_parity(B, orc, dtype, N, K, bits, group):
     assert np.array_equal(host(g["step"]), o["step"].reshape(-1))
     assert np.array_equal(host(g["zero"]), o["zero"].reshape(-1))
     packed = orc.pack_codes(o["codes_u"], bits).view(np.uint8).reshape(-1)
-    assert np.array_equal(host(g["codes"]), packed)
+    got = host(g["codes"])
+    if bits == 8 and group <= 0:
+        got = from_panels(got, N, K).reshape(-1)
+    assert np.array_equal(got, packed)
     if g["rowsum_w"] is not None:
         assert np.array_equal(host(g["rowsum_w"]), o["rowsum_w"])
     assert int(host(g["status"])[0]) == o["status"]
@@ -249,7 +254,7 @@ def test_quant_weight_degenerate_and_half_ties(B, orc):
     z = np.zeros((3, 128), np.float16)
     g = gpu_quant_weight(B, z, 8, 0)
     assert np.all(host(g["step"]) == 1.0) and np.all(host(g["zero"]) == 0)
-    assert np.all(host(g["codes"]).view(np.int8) == -128) and int(host(g["status"])[0]) & B.ST_DEGENERATE
+    assert np.all(from_panels(host(g["codes"]), 3, 128).view(np.int8) == -128) and int(host(g["status"])[0]) & B.ST_DEGENERATE
 
 
 # ------------------------------------------------------------------------------ stage 4a
@@ -257,7 +262,7 @@ def test_quant_weight_degenerate_and_half_ties(B, orc):
 
 def gpu_quant_act(B, X, inv_s, step, zero):
     T, K = X.shape
-    xq = torch.zeros((T, K), dtype=torch.int8, device=DEV)
+    xq = torch.full((B.aweq_panel_bytes(T, K),), 0x5a, dtype=torch.int8, device=DEV)
     rs, cs = e(T, dtype=torch.int32), e(K, dtype=torch.int64)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     B.aweq_quant_act(dev(X), dtc(B, X), T, K, K, dev(inv_s), dev(np.array([step], np.float32)),
@@ -268,7 +273,7 @@ def gpu_quant_act(B, X, inv_s, step, zero):
 def check_quant_act(B, orc, X, inv_s, step, zero):
     o = orc.quant_act(X, inv_s, step, zero)
     g = gpu_quant_act(B, X, inv_s, step, zero)
-    assert np.array_equal(host(g["xq"]), o["xq"])
+    assert np.array_equal(from_panels(host(g["xq"]), *X.shape), o["xq"])
     assert np.array_equal(host(g["rowsum_x"]), o["rowsum_x"])
     assert np.array_equal(host(g["colsum_xq"]), o["colsum_xq"])
     assert int(host(g["status"])[0]) == o["status"]
@@ -327,6 +332,19 @@ def test_quant_act_quotient_paths(B, orc):
     assert o["xq"][5].max() == 127 and o["xq"][6].min() == -128
 
 
+def test_panel_converters(B):
+    progress("K-panel pack / unpack")
+    rng = np.random.default_rng(5)
+    for rows, K, ld in ((300, 200, 208), (64, 64, 64), (5, 8, 8), (1000, 1040, 1040)):
+        m = rng.integers(-128, 128, (rows, ld), dtype=np.int8)
+        panels = torch.full((B.aweq_panel_bytes(rows, K),), 0x5a, dtype=torch.int8, device=DEV)
+        B.aweq_pack_panels_i8(dev(m), rows, K, ld, panels)
+        assert np.array_equal(host(panels), to_panels(m[:, :K]))
+        back = torch.full((rows, ld), 0x5a, dtype=torch.int8, device=DEV)
+        B.aweq_unpack_panels_i8(panels, rows, K, back, ld)
+        assert np.array_equal(host(back)[:, :K], m[:, :K]) and np.all(host(back)[:, K:] == 0x5a)
+
+
 # ------------------------------------------------------------------------------ stage 4b
 
 
@@ -341,10 +359,10 @@ def gpu_gemm(B, xq, wq, want_i32=True, deq=None, colsum=True):
         out_dt = B.AWEQ_F16 if deq["dtype"] == np.float16 else B.AWEQ_F32
         out_deq = torch.zeros((T, N), dtype=torch.float16 if deq["dtype"] == np.float16 else torch.float32, device=DEV)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
-    B.aweq_w8a8_gemm(dev(xq), B.AWEQ_I8, T, K, K, None,
+    B.aweq_w8a8_gemm(dev(to_panels(xq)), B.AWEQ_I8, T, K, K, None,
                      dev(np.array([deq["step_x"]], np.float32)) if deq else None,
                      dev(np.array([deq["zero_x"]], np.int32)) if deq else None,
-                     None, dev(deq["rowsum_x"]) if deq else None, None, dev(wq), N,
+                     None, dev(deq["rowsum_x"]) if deq else None, None, dev(to_panels(wq)), N,
                      dev(deq["step_w"]) if deq else None, dev(deq["zero_w"]) if deq else None,
                      dev(deq["rowsum_w"]) if deq else None, dev(deq["bias"]) if deq and deq["bias"] is not None else None,
                      out, out_deq, out_dt, N, cs, None, status)
@@ -352,17 +370,21 @@ def gpu_gemm(B, xq, wq, want_i32=True, deq=None, colsum=True):
 
 
 @pytest.mark.parametrize("T,N,K", [
-    (256, 256, 64),      # exactly one tile, one k-step
-    (300, 200, 192),     # ragged in both directions
+    (256, 256, 64),      # exactly one tile, one panel
+    (300, 200, 192),     # ragged in both directions, three panels (the ring's prologue only)
+    (260, 256, 128),     # two panels
     (512, 512, 512),     # config-1 weight shape
-    (1000, 700, 1040),   # K not a multiple of the k-step (K % 64 = 16)
+    (1000, 700, 1040),   # K % 64 = 16: zero-filled last panel
     (2048, 1024, 4096),
-    (1, 1, 16),
-    (700, 2100, 128),    # more than one patch along N; one 128-byte stage
-    (1000, 700, 1024),   # K % 128 == 0: LDS-DMA kernel, ragged in both directions
-    (515, 1028, 384),    # LDS-DMA kernel, three stages, ragged
-    (256, 256, 256),
+    (1, 1, 16),          # generic kernel (N % 4 != 0), one partial panel
+    (4, 4, 8),           # LDS-DMA kernel, one partial panel
+    (700, 2100, 128),    # more than one patch along N
+    (1000, 700, 1024),   # ragged in both directions
+    (515, 1028, 384),    # six panels, ragged
+    (256, 256, 256),     # four panels: one pass of the steady-state loop
+    (300, 260, 328),     # K % 64 = 8
     (300, 202, 256),     # N % 4 != 0: falls back to the generic kernel
+    (300, 203, 200),     # generic kernel, zero-filled last panel
 ])
 def test_gemm_parity(B, orc, T, N, K):
     progress(f"gemm T={T} N={N} K={K}")
@@ -379,12 +401,12 @@ def test_gemm_parity(B, orc, T, N, K):
     assert np.array_equal(host(cs2), host(cs))
 
 
-@pytest.mark.parametrize("K", [320, 384])   # generic kernel / LDS-DMA kernel
+@pytest.mark.parametrize("K,N", [(320, 260), (328, 260), (328, 262)])   # ..., zero-filled last panel, generic kernel
 @pytest.mark.parametrize("odt", [np.float32, np.float16])
-def test_gemm_dequant_epilogue(B, orc, odt, K):
-    progress(f"gemm dequant epilogue {odt.__name__} K={K}")
+def test_gemm_dequant_epilogue(B, orc, odt, K, N):
+    progress(f"gemm dequant epilogue {odt.__name__} K={K} N={N}")
     rng = np.random.default_rng(3)
-    T, N = 300, 260
+    T = 300
     xq = rng.integers(-128, 128, (T, K), dtype=np.int8)
     wq = rng.integers(-128, 128, (N, K), dtype=np.int8)
     deq = dict(dtype=odt, step_x=0.0123, zero_x=141, step_w=rng.uniform(1e-4, 1e-3, N).astype(np.float32),
@@ -414,12 +436,12 @@ def test_gemm_with_activation_quantizer_in_front(B, orc):
     q = orc.quant_weight(orc.fold_weight(W, s), 8, 0)
     wq = orc.pack_codes(q["codes_u"], 8)
     a = orc.quant_act(X, inv_s, step, zero)
-    xq, rs, csx = torch.zeros((T, K), dtype=torch.int8, device=DEV), e(T, dtype=torch.int32), e(K, dtype=torch.int64)
+    xq, rs, csx = e(B.aweq_panel_bytes(T, K), dtype=torch.int8), e(T, dtype=torch.int32), e(K, dtype=torch.int64)
     out, csa = e(T, N, dtype=torch.int32), e(N, dtype=torch.int64)
     B.aweq_w8a8_gemm(dev(X), B.AWEQ_F16, T, K, K, dev(inv_s), dev(np.array([step], np.float32)),
-                     dev(np.array([zero], np.int32)), xq, rs, csx, dev(wq), N, None, None, None, None, out, None,
+                     dev(np.array([zero], np.int32)), xq, rs, csx, dev(to_panels(wq)), N, None, None, None, None, out, None,
                      B.AWEQ_F16, N, csa, None, None)
-    assert np.array_equal(host(xq), a["xq"]) and np.array_equal(host(rs), a["rowsum_x"])
+    assert np.array_equal(from_panels(host(xq), T, K), a["xq"]) and np.array_equal(host(rs), a["rowsum_x"])
     ref = orc.gemm_i8(a["xq"], wq)
     assert np.array_equal(host(out), ref)
     assert np.array_equal(host(csa), orc.colsum_acc_from_colsum_xq(wq, a["colsum_xq"]))
@@ -476,7 +498,7 @@ def test_bias_weight_only_parity(B, orc, dtype, K, N, bits, group):
     d_ref, b_ref = orc.bias_wonly(Wh, mu, q["codes_u"], group, q["step"], q["zero"], b_in)
     delta, bout = e(N, dtype=torch.float32), e(N, dtype=torch.float32)
     B.aweq_bias_correct(B.BIAS_WEIGHT_ONLY, dev(Wh), dtc(B, Wh), N, K, K, dev(mu), 96, None, None, None, None, None,
-                        dev(packed), bits, group, dev(q["step"].reshape(-1)), dev(q["zero"].reshape(-1)), dev(b_in),
+                        dev(to_panels(packed.view(np.int8).reshape(N, K)) if bits == 8 and group <= 0 else packed), bits, group, dev(q["step"].reshape(-1)), dev(q["zero"].reshape(-1)), dev(b_in),
                         delta, bout, 1)
     assert np.max(np.abs(host(delta) - d_ref)) <= 1e-5 * np.max(np.abs(d_ref))
     np.testing.assert_allclose(host(bout), b_ref, rtol=1e-5, atol=1e-5 * np.max(np.abs(d_ref)))
@@ -514,15 +536,16 @@ def test_end_to_end_unforced(B, orc, cfg, T, shapes):
         step, zero, _ = orc.qparams(lo, hi, 8)
         np.testing.assert_allclose(host(t["act_step"])[0], step, rtol=1e-5)
         q = orc.quant_weight(Wh, 8, 0)
-        codes = host(t["codes"]).reshape(N, K).astype(np.int32)
+        codes = from_panels(host(t["codes"]), N, K).astype(np.int32)
         ref_codes = orc.pack_codes(q["codes_u"], 8).astype(np.int32)
         diff = np.abs(codes - ref_codes)
         assert diff.max() <= 1 and np.mean(diff != 0) < 1e-3
         a = orc.quant_act(X, inv_s, step, zero)
-        dxq = np.abs(host(t["xq"]).astype(np.int32) - a["xq"].astype(np.int32))
+        gxq = from_panels(host(t["xq"]), T, K)
+        dxq = np.abs(gxq.astype(np.int32) - a["xq"].astype(np.int32))
         assert dxq.max() <= 1 and np.mean(dxq != 0) < 1e-3
         # the GPU's own chain is self-consistent: its GEMM output is exact for its own codes
-        acc = orc.gemm_i8(host(t["xq"]), host(t["codes"]).reshape(N, K))
+        acc = orc.gemm_i8(gxq, from_panels(host(t["codes"]), N, K))
         assert np.array_equal(host(t["out_i32"]), acc)
         wq = orc.pack_codes(q["codes_u"], 8)
         d_ref, b_ref = orc.bias_w8a8(Wh, mu, T, orc.colsum_acc_from_colsum_xq(wq, a["colsum_xq"]), a["colsum_xq"],
@@ -530,7 +553,7 @@ def test_end_to_end_unforced(B, orc, cfg, T, shapes):
         # post-condition on the GPU's own outputs: corrected mean output error vanishes
         Xh = orc.fold_act(X, host(t["inv_s"])).astype(np.float64)
         y_fp = Xh @ host(t["W_hat"]).astype(np.float64).T
-        y_q = orc.w8a8_output_direct(host(t["xq"]), host(t["codes"]).reshape(N, K), host(t["act_step"])[0],
+        y_q = orc.w8a8_output_direct(gxq, from_panels(host(t["codes"]), N, K), host(t["act_step"])[0],
                                      int(host(t["act_zero"])[0]), host(t["step_w"]), host(t["zero_w"]), None)
         resid = (y_q + host(t["delta"]).astype(np.float64) - y_fp).mean(axis=0)
         assert np.max(np.abs(resid)) <= 2e-5 * np.max(np.abs(d_ref)) + 1e-6 * np.max(np.abs(y_fp.mean(axis=0)))

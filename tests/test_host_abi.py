@@ -118,7 +118,7 @@ def test_gemm_and_quant_act_argument_errors(B):
     assert _code(call, wq=None) == "AWEQ_ERR_NULL"
     assert _code(call, xq=None) == "AWEQ_ERR_NULL"        # float input needs the code buffer
     assert _code(call, inv_s=None) == "AWEQ_ERR_NULL"
-    assert _code(call, K=24, ldx=24) == "AWEQ_ERR_SHAPE"
+    assert _code(call, K=20, ldx=20) == "AWEQ_ERR_SHAPE"
     assert _code(call, ldo=16) == "AWEQ_ERR_SHAPE"
     assert _code(call, x_dt=B.AWEQ_I8, ldx=128) == "AWEQ_ERR_SHAPE"
     assert _code(call, out_deq=P, out_dt=B.AWEQ_I8) == "AWEQ_ERR_DTYPE"
@@ -158,3 +158,30 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2311_01305_amd" not in text and "libaweq" not in text, f
+
+
+def test_panel_layout_helpers(B):
+    """aweq_panel_bytes (host) and the argument checks of the converters."""
+    assert B.aweq_panel_bytes(10, 64) == 640 and B.aweq_panel_bytes(10, 72) == 1280 and B.aweq_panel_bytes(3, 8) == 192
+    assert B.aweq_panel_bytes(0, 64) == 0
+    P = 0x10000
+    for fn, args in ((B.aweq_pack_panels_i8, (P, 4, 64, 64, P)), (B.aweq_unpack_panels_i8, (P, 4, 64, P, 64))):
+        ok = list(args)
+        bad_k = list(ok); bad_k[2] = 12
+        with pytest.raises(B.AweqError) as ei:
+            fn(*bad_k, stream=0)
+        assert ei.value.name == "AWEQ_ERR_SHAPE"
+        null = list(ok); null[0] = None
+        with pytest.raises(B.AweqError) as ei:
+            fn(*null, stream=0)
+        assert ei.value.name == "AWEQ_ERR_NULL"
+    with pytest.raises(B.AweqError) as ei:
+        B.aweq_pack_panels_i8(P + 4, 4, 64, 64, P, stream=0)
+    assert ei.value.name == "AWEQ_ERR_ALIGN"
+    # the numpy reference permutation the GPU tests use is its own inverse pair
+    import numpy as np
+    from conftest import from_panels, to_panels
+    m = np.arange(5 * 72, dtype=np.int64).reshape(5, 72).astype(np.int8)
+    p = to_panels(m)
+    assert p.size == B.aweq_panel_bytes(5, 72) and np.array_equal(from_panels(p, 5, 72), m)
+    assert p[64 * 5 + 8] == 0 and p[0:64].tolist() == m[0, :64].tolist() and p[64:128].tolist() == m[1, :64].tolist()
