@@ -24,9 +24,9 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 # on this workload (profiles/gemm_i8_fast_opt6.7b_hbm_traffic.txt), scaled by what the same
 # counters read for a plain 1 GiB device copy (FETCH x2.0, WRITE x1.0).  Keyed by (N, K), T = 262144.
 GEMM_TRAFFIC_BYTES = {
-    (4096, 4096): (6.46e9, 4.44e9),
-    (16384, 4096): (25.8e9, 17.8e9),
-    (4096, 16384): (25.8e9, 4.45e9),
+    (4096, 4096): (6.77e9, 4.57e9),
+    (16384, 4096): (26.5e9, 18.3e9),
+    (4096, 16384): (26.9e9, 4.56e9),
 }
 
 

@@ -64,6 +64,7 @@ struct GemmArgs {
     const int32_t* rowsum_w;
     const float* bias;
     int tiles_m, tiles_n, patch_m, patch_n, patches_n, n_patches;
+    int n_ids;  // workgroup ids that may name a tile (whole rounds of patches over the XCDs)
 };
 
 __global__ __launch_bounds__(kGemmThreads) void gemm_i8_generic(GemmArgs g)
@@ -265,7 +266,7 @@ constexpr int kThreads = 512;
 constexpr int kHalf = BM * kPanel;   // 16 KiB per operand per slot
 constexpr int kSlot = 2 * kHalf;     // 32 KiB: one panel of the A tile and of the B tile
 constexpr int kSlots = 4;
-constexpr int kLds = kSlots * kSlot; // 128 KiB
+constexpr int kLds = kSlots * kSlot + 8 * 4096;  // 128 KiB ring + the epilogue's slabs = 160 KiB
 
 // chunk swizzle for 64-byte slot rows: the four rows r, r + 4, r + 8, r + 12 share LDS banks,
 // so 16 consecutive rows read at one chunk index land on distinct banks
@@ -287,51 +288,42 @@ __device__ __forceinline__ void wait_vm()
 #define SB() __builtin_amdgcn_sched_barrier(0)
 #define MF(A_, B_, i, j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(B_[j], A_[i], acc[i][j], 0, 0, 0)
 
-// DEQ: 0 none, 1 fp32, 2 fp16
+// workgroup id -> output tile (false: the id names no tile).  Ids go round-robin over the XCDs,
+// so id % 8 names the XCD; each XCD walks its own sequence of patch_m x patch_n patches.
+__device__ __forceinline__ bool tile_of(const GemmArgs& g, int vb, int& tile_m, int& tile_n)
+{
+    const int xcd = vb % kXcds, seq = vb / kXcds;
+    const int per_patch = g.patch_m * g.patch_n;
+    const int patch = (seq / per_patch) * kXcds + xcd;
+    if (patch >= g.n_patches) return false;
+    const int within = seq % per_patch;
+    const int pm = patch / g.patches_n, pn = patch % g.patches_n;
+    tile_m = pm * g.patch_m + within % g.patch_m;
+    tile_n = pn * g.patch_n + within / g.patch_m;
+    return tile_m < g.tiles_m && tile_n < g.tiles_n;
+}
+
+// DEQ: 0 none, 1 fp32, 2 fp16.  Persistent: the grid is one workgroup per compute unit
+// (a multiple of 8), workgroup b takes the ids b, b + grid, b + 2 grid, ...; the first panels
+// of its next tile are requested before the epilogue of the current one starts, so the loads
+// fly while the results are stored.
 template <bool I32, int DEQ, bool COLSUM>
 __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
-    const int b = blockIdx.x;
-    const int xcd = b % kXcds, seq = b / kXcds;
-    const int per_patch = g.patch_m * g.patch_n;
-    const int patch = (seq / per_patch) * kXcds + xcd;
-    if (patch >= g.n_patches) return;
-    const int within = seq % per_patch;
-    const int pm = patch / g.patches_n, pn = patch % g.patches_n;
-    const int tile_m = pm * g.patch_m + within % g.patch_m;
-    const int tile_n = pn * g.patch_n + within / g.patch_m;
-    if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
-    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const int stride = gridDim.x;
 
-    // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 16 rows x 64 B
-    // per instruction; lane i sits at row i / 4, chunk slot i % 4 and fetches chunk slot ^ f4(row)
-    uint32_t oa[2], ob[2];  // byte offsets from the tile's first row inside a panel: < 16 KiB
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int row = wave * 32 + q * 16 + (lane >> 2);
-        const int chunk = (lane & 3) ^ f4(row);
-        // rows past the edge re-read the last valid row; their results are never stored
-        const int64_t ra = min(m0 + row, g.T - 1) - m0, rb = min(n0 + row, g.N - 1) - n0;
-        oa[q] = (uint32_t)(ra * kPanel + chunk * 16);
-        ob[q] = (uint32_t)(rb * kPanel + chunk * 16);
-    }
-    const int8_t* srcA = g.A + m0 * kPanel;   // the tile's rows in the panel being fetched
-    const int8_t* srcB = g.B + n0 * kPanel;
+    int vb = blockIdx.x, tile_m = 0, tile_n = 0;
+    while (vb < g.n_ids && !tile_of(g, vb, tile_m, tile_n)) vb += stride;
+    if (vb >= g.n_ids) return;
+
     const int64_t panelA = g.T * kPanel, panelB = g.N * kPanel;
     const int nh = (int)panel_count(g.K);
+    const int pre = nh < 3 ? nh : 3;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
     const uint32_t wave_off = __builtin_amdgcn_readfirstlane(wave) * 2048;
-
-    v16i acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
     // fragment of K-step ks of a panel: lane reads row lane % 32 of a 32-row sub-tile, chunk
     // 2 ks + lane / 32 (sub-tiles start at multiples of 32 rows, so f4(row) = f4(lane % 32))
@@ -342,192 +334,297 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         offA[ks] = (wm * 128 + fr_row) * kPanel + ((ks * 2 + fr_half) ^ f4(fr_row)) * 16;
         offB[ks] = kHalf + (wn * 64 + fr_row) * kPanel + ((ks * 2 + fr_half) ^ f4(fr_row)) * 16;
     }
-    v4i a0[4], b0[2], a1[4], b1[2];
+
+    // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 16 rows x 64 B
+    // per instruction; lane i sits at row i / 4, chunk slot i % 4 and fetches chunk slot ^ f4(row)
+    uint32_t oa[2], ob[2];  // byte offsets from the tile's first row inside a panel: < 16 KiB
+    const int8_t* srcA;     // the tile's rows in the panel being fetched
+    const int8_t* srcB;
+    int64_t m0, n0;
+
+#define DMA_A(q) dma16(srcA, oa[q], dst_slot + (q) * 1024)
+#define DMA_B(q) dma16(srcB, ob[q], dst_slot + kHalf + (q) * 1024)
+    // addresses of tile (tm, tn) and its first `pre` panels on their way into slots 0 ..
+    auto start_tile = [&](int tm, int tn) {
+        // (wave-uniform by construction; say so, the panel base addresses live in scalar registers)
+        m0 = (int64_t)__builtin_amdgcn_readfirstlane(tm) * BM;
+        n0 = (int64_t)__builtin_amdgcn_readfirstlane(tn) * BN;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int row = wave * 32 + q * 16 + (lane >> 2);
+            const int chunk = (lane & 3) ^ f4(row);
+            // rows past the edge re-read the last valid row; their results are never stored
+            const int64_t ra = min(m0 + row, g.T - 1) - m0, rb = min(n0 + row, g.N - 1) - n0;
+            oa[q] = (uint32_t)(ra * kPanel + chunk * 16);
+            ob[q] = (uint32_t)(rb * kPanel + chunk * 16);
+        }
+        srcA = g.A + m0 * kPanel;
+        srcB = g.B + n0 * kPanel;
+        for (int h = 0; h < pre; ++h) {
+            const uint32_t dst_slot = lds0 + h * kSlot + wave_off;
+            DMA_A(0); DMA_B(0); DMA_A(1); DMA_B(1);
+            srcA += panelA; srcB += panelB;
+        }
+    };
+
+    start_tile(tile_m, tile_n);
+    if (pre >= 3) wait_vm<8>(); else if (pre == 2) wait_vm<4>(); else wait_vm<0>();
+
+    // Vector memory operations of a wave complete in the order issued.  A tile that lies inside
+    // the output issues at least kStores stores per wave after requesting the next tile's first
+    // three panels, so "at most kStores operations pending" means those panels have landed
+    // while the stores may still be on their way (relaxed: set for the tile that follows).
+    constexpr int kStoresAll = (I32 ? 32 : 0) + (DEQ != 0 ? 32 : 0);
+    constexpr int kStores = kStoresAll > 63 ? 63 : kStoresAll;
+    bool relaxed = false;
+
+    for (;;) {
+        const int64_t cm0 = m0, cn0 = n0;   // the tile being multiplied
+        v16i acc[4][2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+        v4i a0[4], b0[2], a1[4], b1[2];
 
 #define RDA(dst, ks, i) dst[i] = *reinterpret_cast<const v4i*>(st + offA[ks] + (i) * 32 * kPanel)
 #define RDB(dst, ks, j) dst[j] = *reinterpret_cast<const v4i*>(st + offB[ks] + (j) * 32 * kPanel)
-#define DMA_A(q) dma16(srcA, oa[q], dst_slot + (q) * 1024)
-#define DMA_B(q) dma16(srcB, ob[q], dst_slot + kHalf + (q) * 1024)
-
-    // prologue: up to three panels in flight, the first one landed
-    const int pre = nh < 3 ? nh : 3;
-    for (int h = 0; h < pre; ++h) {
-        const uint32_t dst_slot = lds0 + h * kSlot + wave_off;
-        DMA_A(0); DMA_B(0); DMA_A(1); DMA_B(1);
-        srcA += panelA; srcB += panelB;
-    }
-    if (pre >= 3) wait_vm<8>(); else if (pre == 2) wait_vm<4>(); else wait_vm<0>();
-    __builtin_amdgcn_s_barrier();
-    {
-        const char* st = lds;
+        __builtin_amdgcn_s_barrier();  // panel 0 has landed for every wave
+        {
+            const char* st = lds;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) RDA(a0, 0, i);
-        RDB(b0, 0, 0); RDB(b0, 0, 1);
-    }
-
-    // one panel (64 bytes of K) = two K-steps of 8 MFMAs per wave.  F0 / F1 are the two fragment
-    // register sets; each K-step multiplies one and fetches the other.  ISSUE: panel h + 3 is
-    // fetched into the slot panel h - 1 occupied (every wave finished reading it before the
-    // barrier of panel h - 1).  WAITN: loads this wave may leave in flight when panel h + 1 has
-    // to be complete (4 per panel issued after it).
-    auto half = [&](int h, auto issue_c, auto waitn_c, auto next_c) {
-        constexpr bool ISSUE = decltype(issue_c)::value;
-        constexpr int WAITN = decltype(waitn_c)::value;
-        constexpr bool NEXT = decltype(next_c)::value;
-        const char* st = lds + (h & 3) * kSlot;
-        const uint32_t dst_slot = lds0 + ((h + 3) & 3) * kSlot + wave_off;
-        SB();
-        RDA(a1, 1, 0); RDB(b1, 1, 0); RDB(b1, 1, 1); MF(a0, b0, 0, 0);
-        SB();
-        if constexpr (ISSUE) DMA_A(0);
-        RDA(a1, 1, 1); RDA(a1, 1, 2); MF(a0, b0, 0, 1);
-        SB();
-        if constexpr (ISSUE) DMA_B(0);
-        RDA(a1, 1, 3); MF(a0, b0, 1, 0);
-        SB();
-        if constexpr (ISSUE) DMA_A(1);
-        MF(a0, b0, 1, 1);
-        SB();
-        if constexpr (ISSUE) DMA_B(1);
-        MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
-        SB();
-        if constexpr (ISSUE) { srcA += panelA; srcB += panelB; }
-        if constexpr (NEXT) {
-            // my loads of the next panel have landed, my reads of this one are done; after the
-            // barrier that holds for every wave
-            wait_vm<WAITN>();
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            SB();
-            st = lds + ((h + 1) & 3) * kSlot;
-            RDA(a0, 0, 0); RDB(b0, 0, 0); RDB(b0, 0, 1); MF(a1, b1, 0, 0);
-            SB();
-            RDA(a0, 0, 1); RDA(a0, 0, 2); MF(a1, b1, 0, 1);
-            SB();
-            RDA(a0, 0, 3); MF(a1, b1, 1, 0);
-            SB();
-            MF(a1, b1, 1, 1); MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
-            SB();
-        } else {
-            MF(a1, b1, 0, 0); MF(a1, b1, 0, 1); MF(a1, b1, 1, 0); MF(a1, b1, 1, 1);
-            MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+            for (int i = 0; i < 4; ++i) RDA(a0, 0, i);
+            RDB(b0, 0, 0); RDB(b0, 0, 1);
         }
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using I4 = std::integral_constant<int, 4>;
-    using I8 = std::integral_constant<int, 8>;
-    int h = 0;
-    for (; h + 3 < nh; ++h) half(h, std::true_type{}, I8{}, std::true_type{});
-    if (h + 2 < nh) { half(h, std::false_type{}, I4{}, std::true_type{}); ++h; }
-    if (h + 1 < nh) { half(h, std::false_type{}, I0{}, std::true_type{}); ++h; }
-    half(h, std::false_type{}, I0{}, std::false_type{});
+
+        // one panel (64 bytes of K) = two K-steps of 8 MFMAs per wave.  F0 / F1 are the two
+        // fragment register sets; each K-step multiplies one and fetches the other.  ISSUE: panel
+        // h + 3 is fetched into the slot panel h - 1 occupied (every wave finished reading it before
+        // the barrier of panel h - 1).  WAITN: loads this wave may leave in flight when panel h + 1
+        // has to be complete (4 per panel issued after it).
+        auto half = [&](int h, auto issue_c, auto waitn_c, auto next_c) {
+            constexpr bool ISSUE = decltype(issue_c)::value;
+            constexpr int WAITN = decltype(waitn_c)::value;
+            constexpr bool NEXT = decltype(next_c)::value;
+            const char* st = lds + (h & 3) * kSlot;
+            const uint32_t dst_slot = lds0 + ((h + 3) & 3) * kSlot + wave_off;
+            SB();
+            RDA(a1, 1, 0); RDB(b1, 1, 0); RDB(b1, 1, 1); MF(a0, b0, 0, 0);
+            SB();
+            if constexpr (ISSUE) DMA_A(0);
+            RDA(a1, 1, 1); RDA(a1, 1, 2); MF(a0, b0, 0, 1);
+            SB();
+            if constexpr (ISSUE) DMA_B(0);
+            RDA(a1, 1, 3); MF(a0, b0, 1, 0);
+            SB();
+            if constexpr (ISSUE) DMA_A(1);
+            MF(a0, b0, 1, 1);
+            SB();
+            if constexpr (ISSUE) DMA_B(1);
+            MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
+            SB();
+            if constexpr (ISSUE) { srcA += panelA; srcB += panelB; }
+            if constexpr (NEXT) {
+                // my loads of the next panel have landed, my reads of this one are done; after the
+                // barrier that holds for every wave
+                wait_vm<WAITN>();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                SB();
+                st = lds + ((h + 1) & 3) * kSlot;
+                RDA(a0, 0, 0); RDB(b0, 0, 0); RDB(b0, 0, 1); MF(a1, b1, 0, 0);
+                SB();
+                RDA(a0, 0, 1); RDA(a0, 0, 2); MF(a1, b1, 0, 1);
+                SB();
+                RDA(a0, 0, 3); MF(a1, b1, 1, 0);
+                SB();
+                MF(a1, b1, 1, 1); MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+                SB();
+            } else {
+                MF(a1, b1, 0, 0); MF(a1, b1, 0, 1); MF(a1, b1, 1, 0); MF(a1, b1, 1, 1);
+                MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+            }
+        };
+        using I0 = std::integral_constant<int, 0>;
+        using I4 = std::integral_constant<int, 4>;
+        using I8 = std::integral_constant<int, 8>;
+        using I63 = std::integral_constant<int, 63>;
+        int h = 0;
+        if (relaxed) {
+            // panels 1 and 2 landed together with panel 0: nothing to wait for, and a count of 8
+            // here would wait for the previous tile's stores
+            half(0, std::true_type{}, I63{}, std::true_type{});
+            half(1, std::true_type{}, I63{}, std::true_type{});
+            h = 2;
+        }
+        for (; h + 3 < nh; ++h) half(h, std::true_type{}, I8{}, std::true_type{});
+        if (h + 2 < nh) { half(h, std::false_type{}, I4{}, std::true_type{}); ++h; }
+        if (h + 1 < nh) { half(h, std::false_type{}, I0{}, std::true_type{}); ++h; }
+        half(h, std::false_type{}, I0{}, std::false_type{});
 #undef RDA
 #undef RDB
+
+        // ---- epilogue.  With the weight fragment as first MFMA operand, register v of lane l in
+        // sub-tile (i, j) is token t = m0 + 128 wm + 32 i + l % 32 and output channel
+        // n = n0 + 64 wn + 32 j + 8 (v / 4) + 4 (l / 32) + v % 4: four consecutive n per register quad.
+        // Each wave turns one 32 (t) x 32 (n) sub-tile at a time around in a private 4 KiB LDS slab
+        // (rows of 128 bytes, 16-byte chunks XOR swizzled: conflict-free both ways) so that a lane then
+        // holds 16 bytes of one output row and 8 lanes cover a whole 128-byte line per store.
+        // The slabs live behind the ring, which the next tile's loads are already filling.
+        const int rd_r = lane >> 3, rd_c = lane & 7;
+        const int64_t t_lane = cm0 + wm * 128 + rd_r;   // + 32 i + 8 p
+
+        // everything the epilogue reads from memory is requested before the next tile's panels,
+        // so that waiting for it does not wait for them
+        int rsx[4][4];
+        if constexpr (DEQ != 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int64_t t = t_lane + i * 32 + 8 * p;
+                    rsx[i][p] = t < g.T ? g.rowsum_x[t] : 0;
+                }
+        }
+        Float4 sw[2], bs[2];
+        v4i zr4[2];   // (rowsum_w << 8) | (Z'w & 0xff): |rowsum_w| <= 128 K <= 2^22
+        int zx = 0;
+        float sxf = 0.f;
+        bool n_ok[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t n = cn0 + wn * 64 + 32 * j + rd_c * 4;   // this lane's four channels
+            n_ok[j] = n < g.N;                                     // N % 4 == 0: all four or none
+            if constexpr (DEQ != 0) {
+                sw[j] = bs[j] = Float4{{0.f, 0.f, 0.f, 0.f}};
+                zr4[j] = v4i{0, 0, 0, 0};
+                if (n_ok[j]) {
+                    sw[j] = *reinterpret_cast<const Float4*>(g.step_w + n);
+                    const v4i zw4 = *reinterpret_cast<const v4i*>(g.zero_w + n);
+                    const v4i rw4 = *reinterpret_cast<const v4i*>(g.rowsum_w + n);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) zr4[j][c] = (int)((unsigned)rw4[c] << 8) | ((zw4[c] - 128) & 0xff);
+                    if (g.bias) bs[j] = *reinterpret_cast<const Float4*>(g.bias + n);
+                }
+            }
+        }
+        if constexpr (DEQ != 0) {
+            zx = *g.act_zero - 128;
+            sxf = *g.act_step;
+            // pin the values in registers here: the compiler's wait for them then sits before the
+            // panel requests below, which it cannot see, instead of behind them
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int p = 0; p < 4; ++p) asm volatile("" : "+v"(rsx[i][p]));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    asm volatile("" : "+v"(sw[j].f[c]));
+                    asm volatile("" : "+v"(bs[j].f[c]));
+                    asm volatile("" : "+v"(zr4[j][c]));
+                }
+            zx = __builtin_amdgcn_readfirstlane(zx);
+            sxf = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sxf)));
+        }
+
+        // next tile of this workgroup
+        int nvb = vb + stride, ntm = 0, ntn = 0;
+        while (nvb < g.n_ids && !tile_of(g, nvb, ntm, ntn)) nvb += stride;
+        const bool more = nvb < g.n_ids;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();  // every wave is done reading the ring
+        if (more) start_tile(ntm, ntn);
+
+        char* slab = lds + kSlots * kSlot + wave * 4096;
+        const int wr_t = lane & 31;
+        const int wr_off = wr_t * 128;                       // chunk (2 q + l / 32) ^ ((t >> 1) & 7)
+        const int wr_sw = (wr_t >> 1) & 7, wr_half = lane >> 5;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t n = cn0 + wn * 64 + 32 * j + rd_c * 4;
+            // per-channel constants of the de-quantisation
+            double scale[4] = {0, 0, 0, 0}, bsd[4] = {0, 0, 0, 0};
+            unsigned cn[4] = {0, 0, 0, 0}, zw[4] = {0, 0, 0, 0};
+            if constexpr (DEQ != 0) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    zw[c] = (unsigned)(int)(int8_t)(zr4[j][c] & 0xff);
+                    scale[c] = (double)sxf * (double)sw[j].f[c];
+                    bsd[c] = (double)bs[j].f[c];
+                    // integer part in wrap-around 32-bit arithmetic: the final value fits (|.| <= 255^2 K)
+                    cn[c] = (unsigned)g.K * (unsigned)zx * zw[c] - (unsigned)zx * (unsigned)(zr4[j][c] >> 8);
+                }
+            }
+            long long csum[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v4i o = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    *reinterpret_cast<v4i*>(slab + wr_off + (((2 * q + wr_half) ^ wr_sw) * 16)) = o;
+                }
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int r = 8 * p + rd_r;
+                    const v4i o = *reinterpret_cast<const v4i*>(slab + r * 128 + ((rd_c ^ ((r >> 1) & 7)) * 16));
+                    const int64_t t = t_lane + i * 32 + 8 * p;
+                    if (t < g.T && n_ok[j]) {
+                        if constexpr (I32) __builtin_nontemporal_store(o, reinterpret_cast<v4i*>(g.out_i32 + t * g.ldo + n));
+                        if constexpr (DEQ != 0) {
+                            const unsigned rs = (unsigned)rsx[i][p];
+                            float y[4];
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const unsigned iv = (unsigned)o[c] + cn[c] - zw[c] * rs;
+                                y[c] = (float)((double)(int)iv * scale[c] + bsd[c]);
+                            }
+                            if constexpr (DEQ == 2) {
+                                typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                                h4 oh = {(_Float16)y[0], (_Float16)y[1], (_Float16)y[2], (_Float16)y[3]};
+                                __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out_deq) + t * g.ldo + n));
+                            } else {
+                                typedef float f4 __attribute__((ext_vector_type(4)));
+                                f4 of = {y[0], y[1], y[2], y[3]};
+                                __builtin_nontemporal_store(of, reinterpret_cast<f4*>(reinterpret_cast<float*>(g.out_deq) + t * g.ldo + n));
+                            }
+                        }
+                        if constexpr (COLSUM) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) csum[c] += o[c];
+                        }
+                    }
+                }
+            }
+            if constexpr (COLSUM) {
+                // lanes l, l ^ 8, l ^ 16, l ^ 32 hold the same channels for different tokens
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    int lo = (int)(csum[c] & 0xffffffffll), hi = (int)(csum[c] >> 32);
+                    long long s8 = ((long long)xor8(hi) << 32) | (unsigned int)xor8(lo);
+                    csum[c] += s8;
+                    csum[c] += partner<4>(csum[c]);
+                    csum[c] += partner<5>(csum[c]);
+                }
+                if (lane < 8 && n_ok[j]) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        atomicAdd(reinterpret_cast<unsigned long long*>(&g.colsum_acc[n + c]), (unsigned long long)csum[c]);
+                }
+            }
+        }
+        if (!more) break;
+        vb = nvb;
+        // the panels requested before the epilogue have landed
+        relaxed = kStores > 0 && nh >= 6 && cm0 + BM <= g.T && cn0 + BN <= g.N;
+        if (relaxed) wait_vm<kStores>();
+        else wait_vm<0>();
+    }
 #undef DMA_A
 #undef DMA_B
-
-    // ---- epilogue.  With the weight fragment as first MFMA operand, register v of lane l in
-    // sub-tile (i, j) is token t = m0 + 128 wm + 32 i + l % 32 and output channel
-    // n = n0 + 64 wn + 32 j + 8 (v / 4) + 4 (l / 32) + v % 4: four consecutive n per register quad.
-    // Each wave turns its 32 (t) x 64 (n) slab of sub-tile row i around in a private LDS region
-    // (row pitch 272 bytes: conflict-free both ways) so that a lane then holds 16 bytes of one
-    // output row and 16 lanes cover 256 contiguous bytes: whole cache lines per store.
-    constexpr int kPitch = 64 * 4 + 16;
-    __syncthreads();  // every wave is done with the stage buffers
-    char* slab = lds + wave * (32 * kPitch);
-    const int wr_off = (lane & 31) * kPitch + (lane >> 5) * 16;  // + (32 j + 8 q) * 4
-    const int rd_r = lane >> 4, rd_c = lane & 15;
-    const int rd_off = rd_r * kPitch + rd_c * 16;                // + 4 p * kPitch
-    const int64_t n = n0 + wn * 64 + rd_c * 4;                   // this lane's four channels
-    const bool n_ok = n < g.N;                                   // N % 4 == 0: all four or none
-    const int64_t t_wave = m0 + wm * 128 + rd_r;
-
-    // per-channel constants of the de-quantisation
-    double scale[4] = {0, 0, 0, 0}, bsd[4] = {0, 0, 0, 0};
-    unsigned cn[4] = {0, 0, 0, 0}, zw[4] = {0, 0, 0, 0};
-    if constexpr (DEQ != 0) {
-        if (n_ok) {
-            const int zx = *g.act_zero - 128;
-            const double sx = (double)*g.act_step;
-            const Float4 sw = *reinterpret_cast<const Float4*>(g.step_w + n);
-            const v4i zw4 = *reinterpret_cast<const v4i*>(g.zero_w + n);
-            const v4i rw4 = *reinterpret_cast<const v4i*>(g.rowsum_w + n);
-            Float4 bs = {{0.f, 0.f, 0.f, 0.f}};
-            if (g.bias) bs = *reinterpret_cast<const Float4*>(g.bias + n);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                zw[c] = (unsigned)(zw4[c] - 128);
-                scale[c] = sx * (double)sw.f[c];
-                bsd[c] = (double)bs.f[c];
-                // integer part in wrap-around 32-bit arithmetic: the final value fits (|.| <= 255^2 K)
-                cn[c] = (unsigned)g.K * (unsigned)zx * zw[c] - (unsigned)zx * (unsigned)rw4[c];
-            }
-        }
-    }
-    long long csum[4] = {0, 0, 0, 0};
-
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                v4i o = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                *reinterpret_cast<v4i*>(slab + wr_off + (32 * j + 8 * q) * 4) = o;
-            }
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            const v4i o = *reinterpret_cast<const v4i*>(slab + rd_off + 4 * p * kPitch);
-            const int64_t t = t_wave + i * 32 + 4 * p;
-            if (t < g.T && n_ok) {
-                if constexpr (I32) __builtin_nontemporal_store(o, reinterpret_cast<v4i*>(g.out_i32 + t * g.ldo + n));
-                if constexpr (DEQ != 0) {
-                    const unsigned rsx = (unsigned)g.rowsum_x[t];
-                    float y[4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const unsigned iv = (unsigned)o[c] + cn[c] - zw[c] * rsx;
-                        y[c] = (float)((double)(int)iv * scale[c] + bsd[c]);
-                    }
-                    if constexpr (DEQ == 2) {
-                        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                        h4 oh = {(_Float16)y[0], (_Float16)y[1], (_Float16)y[2], (_Float16)y[3]};
-                        __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out_deq) + t * g.ldo + n));
-                    } else {
-                        typedef float f4 __attribute__((ext_vector_type(4)));
-                        f4 of = {y[0], y[1], y[2], y[3]};
-                        __builtin_nontemporal_store(of, reinterpret_cast<f4*>(reinterpret_cast<float*>(g.out_deq) + t * g.ldo + n));
-                    }
-                }
-                if constexpr (COLSUM) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) csum[c] += o[c];
-                }
-            }
-        }
-    }
-
-    if constexpr (COLSUM) {
-        // lanes l, l ^ 16, l ^ 32 hold the same channels for different tokens; then the two
-        // waves stacked along t meet in LDS and one of them adds to the global sums
-        long long* tot = reinterpret_cast<long long*>(lds + 8 * 32 * kPitch);  // [wn][64]
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            csum[c] += partner<4>(csum[c]);
-            csum[c] += partner<5>(csum[c]);
-        }
-        if (wm == 1 && lane < 16) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) tot[wn * 64 + lane * 4 + c] = csum[c];
-        }
-        __syncthreads();
-        if (wm == 0 && lane < 16 && n_ok) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                atomicAdd(reinterpret_cast<unsigned long long*>(&g.colsum_acc[n + c]),
-                          (unsigned long long)(csum[c] + tot[wn * 64 + lane * 4 + c]));
-        }
-    }
 }
 #undef SB
 #undef MF
@@ -608,6 +705,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     const int64_t rounds = cdiv(g.n_patches, kXcds);
     const int64_t blocks = rounds * kXcds * g.patch_m * g.patch_n;
     if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+    g.n_ids = (int)blocks;
 
     if (colsum_acc) zero_fill_u32_gemm<<<(unsigned)cdiv(2 * N, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_acc), 2 * N);
 
@@ -627,7 +725,15 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
 #undef AWEQ_PICK
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, fast::kLds) != hipSuccess) return AWEQ_ERR_LAUNCH;
         void* args[] = {&g};
-        if (hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(fast::kThreads), args, fast::kLds, st) != hipSuccess) return AWEQ_ERR_LAUNCH;
+        // persistent: one workgroup per compute unit (a multiple of 8, so that id % 8 stays the XCD)
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return AWEQ_ERR_LAUNCH;
+        int64_t grid = (cus / kXcds) * kXcds;
+        if (grid < kXcds) grid = kXcds;
+        if (grid > blocks) grid = blocks;
+        g.n_ids = (int)blocks;
+        if (hipLaunchKernel(fn, dim3((unsigned)grid), dim3(fast::kThreads), args, fast::kLds, st) != hipSuccess) return AWEQ_ERR_LAUNCH;
         return launch_status();
     }
     const size_t lds_bytes = 2 * 2 * kTileBytes;  // 64 KiB
