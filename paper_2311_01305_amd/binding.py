@@ -36,6 +36,9 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # torch brings its own HIP runtime; it has to be the one already in the process when
+    # libaweq.so resolves its runtime symbols, or streams and kernels end up in two runtimes
+    import torch  # noqa: F401
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2311_01305_amd.build` "
                           "(there is no CPU fallback)")

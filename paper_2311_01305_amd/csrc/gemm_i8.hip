@@ -266,7 +266,7 @@ constexpr int kThreads = 512;
 constexpr int kHalf = BM * kPanel;   // 16 KiB per operand per slot
 constexpr int kSlot = 2 * kHalf;     // 32 KiB: one panel of the A tile and of the B tile
 constexpr int kSlots = 4;
-constexpr int kLds = kSlots * kSlot + 8 * 4096;  // 128 KiB ring + the epilogue's slabs = 160 KiB
+constexpr int kLds = kSlots * kSlot + 32768;  // 128 KiB ring + 32 KiB: the epilogue's slabs use the last slot and the tail = 160 KiB
 
 // chunk swizzle for 64-byte slot rows: the four rows r, r + 4, r + 8, r + 12 share LDS banks,
 // so 16 consecutive rows read at one chunk index land on distinct banks
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
     // the output issues at least kStores stores per wave after requesting the next tile's first
     // three panels, so "at most kStores operations pending" means those panels have landed
     // while the stores may still be on their way (relaxed: set for the tile that follows).
-    constexpr int kStoresAll = (I32 ? 32 : 0) + (DEQ != 0 ? 32 : 0);
+    constexpr int kStoresAll = (I32 ? 32 : 0) + (DEQ != 0 ? 32 : 0);   // 4 sub-tile rows x 8 passes each
     constexpr int kStores = kStoresAll > 63 ? 63 : kStoresAll;
     bool relaxed = false;
 
@@ -469,64 +469,49 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         // ---- epilogue.  With the weight fragment as first MFMA operand, register v of lane l in
         // sub-tile (i, j) is token t = m0 + 128 wm + 32 i + l % 32 and output channel
         // n = n0 + 64 wn + 32 j + 8 (v / 4) + 4 (l / 32) + v % 4: four consecutive n per register quad.
-        // Each wave turns one 32 (t) x 32 (n) sub-tile at a time around in a private 4 KiB LDS slab
-        // (rows of 128 bytes, 16-byte chunks XOR swizzled: conflict-free both ways) so that a lane then
-        // holds 16 bytes of one output row and 8 lanes cover a whole 128-byte line per store.
-        // The slabs live behind the ring, which the next tile's loads are already filling.
-        const int rd_r = lane >> 3, rd_c = lane & 7;
-        const int64_t t_lane = cm0 + wm * 128 + rd_r;   // + 32 i + 8 p
+        // Each wave turns its 32 (t) x 64 (n) slab of sub-tile row i around in a private 8 KiB LDS
+        // region (rows of 256 bytes, 16-byte chunks XOR swizzled: conflict-free both ways) so that a
+        // lane then holds 16 bytes of one output row and 16 lanes cover 256 contiguous bytes per store.
+        // The slabs live in the last ring slot and behind the ring; the next tile's first three
+        // panels are already on their way into the other slots.
+        const int rd_r = lane >> 4, rd_c = lane & 15;
+        const int64_t t_lane = cm0 + wm * 128 + rd_r;              // + 32 i + 4 p
+        const int64_t n = cn0 + wn * 64 + rd_c * 4;                // this lane's four channels
+        const bool n_ok = n < g.N;                                 // N % 4 == 0: all four or none
 
         // everything the epilogue reads from memory is requested before the next tile's panels,
         // so that waiting for it does not wait for them
-        int rsx[4][4];
-        if constexpr (DEQ != 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const int64_t t = t_lane + i * 32 + 8 * p;
-                    rsx[i][p] = t < g.T ? g.rowsum_x[t] : 0;
-                }
-        }
-        Float4 sw[2], bs[2];
-        v4i zr4[2];   // (rowsum_w << 8) | (Z'w & 0xff): |rowsum_w| <= 128 K <= 2^22
+        int rsx[2] = {0, 0};   // row sums of this wave's 128 tokens, two per lane: token 64 h + lane
+        Float4 sw = {{0.f, 0.f, 0.f, 0.f}}, bs = {{0.f, 0.f, 0.f, 0.f}};
+        v4i zr4 = {0, 0, 0, 0};   // (rowsum_w << 8) | (Z'w & 0xff): |rowsum_w| <= 128 K <= 2^22
         int zx = 0;
         float sxf = 0.f;
-        bool n_ok[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t n = cn0 + wn * 64 + 32 * j + rd_c * 4;   // this lane's four channels
-            n_ok[j] = n < g.N;                                     // N % 4 == 0: all four or none
-            if constexpr (DEQ != 0) {
-                sw[j] = bs[j] = Float4{{0.f, 0.f, 0.f, 0.f}};
-                zr4[j] = v4i{0, 0, 0, 0};
-                if (n_ok[j]) {
-                    sw[j] = *reinterpret_cast<const Float4*>(g.step_w + n);
-                    const v4i zw4 = *reinterpret_cast<const v4i*>(g.zero_w + n);
-                    const v4i rw4 = *reinterpret_cast<const v4i*>(g.rowsum_w + n);
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) zr4[j][c] = (int)((unsigned)rw4[c] << 8) | ((zw4[c] - 128) & 0xff);
-                    if (g.bias) bs[j] = *reinterpret_cast<const Float4*>(g.bias + n);
-                }
-            }
-        }
         if constexpr (DEQ != 0) {
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int64_t t = cm0 + wm * 128 + hh * 64 + lane;
+                rsx[hh] = t < g.T ? g.rowsum_x[t] : 0;
+            }
+            if (n_ok) {
+                sw = *reinterpret_cast<const Float4*>(g.step_w + n);
+                const v4i zw4 = *reinterpret_cast<const v4i*>(g.zero_w + n);
+                const v4i rw4 = *reinterpret_cast<const v4i*>(g.rowsum_w + n);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) zr4[c] = (int)((unsigned)rw4[c] << 8) | ((zw4[c] - 128) & 0xff);
+                if (g.bias) bs = *reinterpret_cast<const Float4*>(g.bias + n);
+            }
             zx = *g.act_zero - 128;
             sxf = *g.act_step;
             // pin the values in registers here: the compiler's wait for them then sits before the
             // panel requests below, which it cannot see, instead of behind them
+            asm volatile("" : "+v"(rsx[0]));
+            asm volatile("" : "+v"(rsx[1]));
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int p = 0; p < 4; ++p) asm volatile("" : "+v"(rsx[i][p]));
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    asm volatile("" : "+v"(sw[j].f[c]));
-                    asm volatile("" : "+v"(bs[j].f[c]));
-                    asm volatile("" : "+v"(zr4[j][c]));
-                }
+            for (int c = 0; c < 4; ++c) {
+                asm volatile("" : "+v"(sw.f[c]));
+                asm volatile("" : "+v"(bs.f[c]));
+                asm volatile("" : "+v"(zr4[c]));
+            }
             zx = __builtin_amdgcn_readfirstlane(zx);
             sxf = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sxf)));
         }
@@ -539,81 +524,78 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         __builtin_amdgcn_s_barrier();  // every wave is done reading the ring
         if (more) start_tile(ntm, ntn);
 
-        char* slab = lds + kSlots * kSlot + wave * 4096;
-        const int wr_t = lane & 31;
-        const int wr_off = wr_t * 128;                       // chunk (2 q + l / 32) ^ ((t >> 1) & 7)
-        const int wr_sw = (wr_t >> 1) & 7, wr_half = lane >> 5;
+        // per-channel constants of the de-quantisation
+        double scale[4] = {0, 0, 0, 0}, bsd[4] = {0, 0, 0, 0};
+        unsigned cn[4] = {0, 0, 0, 0}, zw[4] = {0, 0, 0, 0};
+        if constexpr (DEQ != 0) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t n = cn0 + wn * 64 + 32 * j + rd_c * 4;
-            // per-channel constants of the de-quantisation
-            double scale[4] = {0, 0, 0, 0}, bsd[4] = {0, 0, 0, 0};
-            unsigned cn[4] = {0, 0, 0, 0}, zw[4] = {0, 0, 0, 0};
-            if constexpr (DEQ != 0) {
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    zw[c] = (unsigned)(int)(int8_t)(zr4[j][c] & 0xff);
-                    scale[c] = (double)sxf * (double)sw[j].f[c];
-                    bsd[c] = (double)bs[j].f[c];
-                    // integer part in wrap-around 32-bit arithmetic: the final value fits (|.| <= 255^2 K)
-                    cn[c] = (unsigned)g.K * (unsigned)zx * zw[c] - (unsigned)zx * (unsigned)(zr4[j][c] >> 8);
-                }
+            for (int c = 0; c < 4; ++c) {
+                zw[c] = (unsigned)(int)(int8_t)(zr4[c] & 0xff);
+                scale[c] = (double)sxf * (double)sw.f[c];
+                bsd[c] = (double)bs.f[c];
+                // integer part in wrap-around 32-bit arithmetic: the final value fits (|.| <= 255^2 K)
+                cn[c] = (unsigned)g.K * (unsigned)zx * zw[c] - (unsigned)zx * (unsigned)(zr4[c] >> 8);
             }
-            long long csum[4] = {0, 0, 0, 0};
+        }
+        char* slab = lds + 3 * kSlot + wave * 8192;
+        const int wr_t = lane & 31;
+        const int wr_sw = wr_t & 15, wr_half = lane >> 5;           // chunk (8 j + 2 q + l / 32) ^ (t & 15)
+        long long csum[4] = {0, 0, 0, 0};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     v4i o = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                    *reinterpret_cast<v4i*>(slab + wr_off + (((2 * q + wr_half) ^ wr_sw) * 16)) = o;
+                    *reinterpret_cast<v4i*>(slab + wr_t * 256 + (((8 * j + 2 * q + wr_half) ^ wr_sw) * 16)) = o;
                 }
 #pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const int r = 8 * p + rd_r;
-                    const v4i o = *reinterpret_cast<const v4i*>(slab + r * 128 + ((rd_c ^ ((r >> 1) & 7)) * 16));
-                    const int64_t t = t_lane + i * 32 + 8 * p;
-                    if (t < g.T && n_ok[j]) {
-                        if constexpr (I32) __builtin_nontemporal_store(o, reinterpret_cast<v4i*>(g.out_i32 + t * g.ldo + n));
-                        if constexpr (DEQ != 0) {
-                            const unsigned rs = (unsigned)rsx[i][p];
-                            float y[4];
+            for (int p = 0; p < 8; ++p) {
+                const int r = 4 * p + rd_r;
+                const v4i o = *reinterpret_cast<const v4i*>(slab + r * 256 + ((rd_c ^ (r & 15)) * 16));
+                const int64_t t = t_lane + i * 32 + 4 * p;
+                unsigned rs = 0;
+                // row sum of token 32 i + 4 p + lane / 16 of the wave: held by lane (that % 64), half
+                // i / 2 (fetched with every lane active: a switched-off source lane would read as 0)
+                if constexpr (DEQ != 0) rs = (unsigned)__builtin_amdgcn_ds_bpermute((((i & 1) * 32 + 4 * p + rd_r) & 63) * 4, rsx[i >> 1]);
+                if (t < g.T && n_ok) {
+                    if constexpr (I32) __builtin_nontemporal_store(o, reinterpret_cast<v4i*>(g.out_i32 + t * g.ldo + n));
+                    if constexpr (DEQ != 0) {
+                        float y[4];
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                const unsigned iv = (unsigned)o[c] + cn[c] - zw[c] * rs;
-                                y[c] = (float)((double)(int)iv * scale[c] + bsd[c]);
-                            }
-                            if constexpr (DEQ == 2) {
-                                typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                                h4 oh = {(_Float16)y[0], (_Float16)y[1], (_Float16)y[2], (_Float16)y[3]};
-                                __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out_deq) + t * g.ldo + n));
-                            } else {
-                                typedef float f4 __attribute__((ext_vector_type(4)));
-                                f4 of = {y[0], y[1], y[2], y[3]};
-                                __builtin_nontemporal_store(of, reinterpret_cast<f4*>(reinterpret_cast<float*>(g.out_deq) + t * g.ldo + n));
-                            }
+                        for (int c = 0; c < 4; ++c) {
+                            const unsigned iv = (unsigned)o[c] + cn[c] - zw[c] * rs;
+                            y[c] = (float)((double)(int)iv * scale[c] + bsd[c]);
                         }
-                        if constexpr (COLSUM) {
+                        if constexpr (DEQ == 2) {
+                            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                            h4 oh = {(_Float16)y[0], (_Float16)y[1], (_Float16)y[2], (_Float16)y[3]};
+                            __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out_deq) + t * g.ldo + n));
+                        } else {
+                            typedef float f4 __attribute__((ext_vector_type(4)));
+                            f4 of = {y[0], y[1], y[2], y[3]};
+                            __builtin_nontemporal_store(of, reinterpret_cast<f4*>(reinterpret_cast<float*>(g.out_deq) + t * g.ldo + n));
+                        }
+                    }
+                    if constexpr (COLSUM) {
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) csum[c] += o[c];
-                        }
+                        for (int c = 0; c < 4; ++c) csum[c] += o[c];
                     }
                 }
             }
-            if constexpr (COLSUM) {
-                // lanes l, l ^ 8, l ^ 16, l ^ 32 hold the same channels for different tokens
+        }
+        if constexpr (COLSUM) {
+            // lanes l, l ^ 16, l ^ 32 hold the same channels for different tokens
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    int lo = (int)(csum[c] & 0xffffffffll), hi = (int)(csum[c] >> 32);
-                    long long s8 = ((long long)xor8(hi) << 32) | (unsigned int)xor8(lo);
-                    csum[c] += s8;
-                    csum[c] += partner<4>(csum[c]);
-                    csum[c] += partner<5>(csum[c]);
-                }
-                if (lane < 8 && n_ok[j]) {
+            for (int c = 0; c < 4; ++c) {
+                csum[c] += partner<4>(csum[c]);
+                csum[c] += partner<5>(csum[c]);
+            }
+            if (lane < 16 && n_ok) {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        atomicAdd(reinterpret_cast<unsigned long long*>(&g.colsum_acc[n + c]), (unsigned long long)csum[c]);
-                }
+                for (int c = 0; c < 4; ++c)
+                    atomicAdd(reinterpret_cast<unsigned long long*>(&g.colsum_acc[n + c]), (unsigned long long)csum[c]);
             }
         }
         if (!more) break;
