@@ -39,12 +39,95 @@ def parse():
     ap.add_argument("--tokens", type=int, default=0, help="override the number of calibration tokens (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-deq", action="store_true", help="GEMM writes the de-quantised fp16 output instead of int32")
+    ap.add_argument("--weight-only", type=int, default=0, choices=(0, 3, 4),
+                    help="weight-only calibration (BASELINE.json configs[3]): W4 or W3 per group of 128, fp16 activations "
+                         "(statistics, equalization, weight quantizer, bias correction; no GEMM); implies --cfg 4")
     ap.add_argument("--layers", default="", help="comma-separated layer names to keep (profiling runs)")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="only measure the sustained shader clock / MFMA rate for three kinds of operand data and exit")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="only run a plain device copy of this many bytes (reference for the HBM counters) and exit")
     return ap.parse_args()
+
+
+def weight_only_bench(args, torch, B, pipeline, synth, dev):
+    """configs[3]: every linear of the LLaMA-7B-shaped block through statistics, equalization,
+    the W4 / W3 group-128 weight quantizer and the weight-only bias correction."""
+    wl = synth.WORKLOADS[4]
+    T = args.tokens or wl.T
+    bits = args.weight_only
+    layers = []
+    for li, lin in enumerate(wl.linears):
+        seed = synth.layer_seed(wl.cfg, li)
+        X = synth.make_act_torch(seed, T, lin.K, wl, dev)
+        W = synth.make_weight_torch(seed, lin.N, lin.K, wl.dtype, dev)
+        buf = pipeline.LayerBuffers(T, lin.K, lin.N, torch.float16, bits=bits, group=128, w8a8=False, device=dev)
+        layers.append((lin, X, W, buf))
+    torch.cuda.synchronize()
+    dt = B.AWEQ_F16
+    stages = ("stats_x", "stats_w", "equalize", "quant_weight", "bias")
+
+    def run_layer(lin, X, W, buf, ev=None):
+        t, K, N, st = buf.t, lin.K, lin.N, buf.t["status"]
+
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        B.aweq_calib_stats(X, dt, T, K, K, t["xmin"], t["xmax"], t["xsum"], t["count"], 0, 1, t["r_x"], t["R_x"],
+                           t["p_x"], t["ws"], st)
+        mark(1)
+        B.aweq_calib_stats(W, dt, N, K, K, t["wmin"], t["wmax"], None, t["wcount"], 0, 1, t["r_w"], t["R_w"],
+                           t["p_w"], t["ws"], st)
+        mark(2)
+        B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, 1, t["s"], t["inv_s"], W,
+                        t["W_hat"], dt, N, K, None, t["xhat_range"], t["mu_xhat"], t["act_step"], t["act_zero"], st)
+        mark(3)
+        B.aweq_quant_weight(t["W_hat"], dt, N, K, K, bits, 128, t["codes"], t["step_w"], t["zero_w"], None, t["ws"], st)
+        mark(4)
+        B.aweq_bias_correct(B.BIAS_WEIGHT_ONLY, t["W_hat"], dt, N, K, K, t["mu_xhat"], T, None, None, None, None, None,
+                            t["codes"], bits, 128, t["step_w"], t["zero_w"], None, t["delta"], t["bias_out"], 1, None, st)
+        mark(5)
+
+    for _ in range(args.warmup):
+        for lay in layers:
+            run_layer(*lay)
+    torch.cuda.synchronize()
+    evs = [[[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in layers] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        for i, lay in enumerate(layers):
+            run_layer(*lay, evs[k][i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    per_layer, sx_ms, sx_bytes = [], 0.0, 0.0
+    for i, (lin, *_r) in enumerate(layers):
+        ms = {s: sum(evs[k][i][j].elapsed_time(evs[k][i][j + 1]) for k in range(args.steps)) / args.steps
+              for j, s in enumerate(stages)}
+        sx_ms += ms["stats_x"]
+        sx_bytes += 2.0 * T * lin.K
+        per_layer.append({"name": lin.name, "N": lin.N, "K": lin.K, "ms": {s: round(v, 4) for s, v in ms.items()},
+                          "stats_x_GBs": round(2.0 * T * lin.K / (ms["stats_x"] * 1e-3) / 1e9, 1)})
+    status_bits = 0
+    for *_r, buf in layers:
+        status_bits |= int(buf.t["status"].item())
+    achieved = sx_bytes / (sx_ms * 1e-3) / 1e9
+    return {
+        "metric": "calibration tokens/sec per layer (stats+equalize+quant+bias); W8A8 GEMM TOPS",
+        "value": len(layers) * T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"cfg4 {wl.name}: {len(layers)} linears, T={T} calibration tokens, f16, weight-only "
+                               f"W{bits} per group of 128, fp16 activations, equalization + bias correction; no GEMM in "
+                               "this configuration",
+                   "value_is": "layers * T / step time over statistics, equalization, weight quantizer, bias correction"},
+        "roofline": {"bound": "hbm", "kernel": "col_stats_partial_f16 (+ merge, finalize: the whole aweq_calib_stats call on X)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None,
+                     "note": "achieved = 2 B x T x K of X over the event-timed aweq_calib_stats calls (3 kernels each)"},
+        "layers": per_layer, "status_bits": status_bits,
+    }
 
 
 def cpu_baseline(wl, lin, seed, tokens):
@@ -124,6 +207,9 @@ def main():
         ms = e0.elapsed_time(e1) / 5
         print(json.dumps({"copy_probe_bytes": args.copy_probe, "ms": ms,
                           "GBs_read_plus_write": 2 * args.copy_probe / ms / 1e6}))
+        return
+    if args.weight_only:
+        print(json.dumps(weight_only_bench(args, torch, B, pipeline, synth, dev)))
         return
     wl = synth.WORKLOADS[args.cfg]
     T = args.tokens or wl.T

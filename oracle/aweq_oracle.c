@@ -390,6 +390,47 @@ void orc_dequant_weight(const uint8_t* codes_u, int64_t N, int64_t K, int64_t gr
         }
 }
 
+/* The same W-tilde as the binary16 operand a half-precision matrix unit consumes in the
+ * weight-only forward (Sec. 4.2: INT3 / INT4 weights, FP16 activations): Step is first
+ * rounded to binary16, the product (u - Z) * Step_h is one binary32 multiplication and the
+ * result is rounded to binary16.  (For |u - Z| <= 2048 the product is exact in binary32,
+ * so this is the correctly rounded binary16 value of (u - Z) * Step_h.) */
+void orc_dequant_weight_h(const uint8_t* codes_u, int64_t N, int64_t K, int64_t group,
+                          const float* step, const int32_t* zero, uint16_t* W_tilde_h)
+{
+    const int64_t g = group > 0 ? group : K;
+    const int64_t ng = K / g;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t pi = group < 0 ? 0 : (group == 0 ? n : n * ng + k / g);
+            float step_h = orc_h2f(orc_f2h(step[pi]));
+            float w = (float)((int32_t)codes_u[n * K + k] - zero[pi]) * step_h;
+            W_tilde_h[n * K + k] = orc_f2h(w);
+        }
+}
+
+/* Weight-only forward: y[t,n] = sum_k x_hat[t,k] w~_h[n,k] + b[n] with binary16 operands,
+ * summed here in fp64 in the order of k; abs_y[t,n] = sum_k |x_hat w~_h| (+ |b|) is the
+ * magnitude a floating-point accumulation error bound scales with.  bias / abs_y nullable. */
+void orc_wonly_forward(const uint16_t* X_hat_h, int64_t T, int64_t K, int64_t ldx,
+                       const uint16_t* W_tilde_h, int64_t N, const float* bias,
+                       double* y, double* abs_y)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0, mag = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double p = (double)orc_h2f(X_hat_h[t * ldx + k]) * (double)orc_h2f(W_tilde_h[n * K + k]);
+                acc += p;
+                mag += fabs(p);
+            }
+            if (bias) { acc += (double)bias[n]; mag += fabs((double)bias[n]); }
+            y[t * N + n] = acc;
+            if (abs_y) abs_y[t * N + n] = mag;
+        }
+}
+
 /* ------------------------------------------------------- stage 4: W8A8 activation + GEMM */
 
 /* Static per-tensor int8 activation quantizer applied to X_hat = X * inv_s (Eq. 1 with

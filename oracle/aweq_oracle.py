@@ -221,6 +221,30 @@ def dequant_weight(codes_u, group, step, zero):
     return out
 
 
+def dequant_weight_h(codes_u, group, step, zero):
+    """-> binary16 W-tilde as the weight-only forward consumes it (Step rounded to binary16)."""
+    codes_u = _c(codes_u, np.uint8)
+    N, K = codes_u.shape
+    out = np.empty((N, K), np.float16)
+    lib().orc_dequant_weight_h(_p(codes_u), i64(N), i64(K), i64(group), _p(_c(step, np.float32)),
+                               _p(_c(zero, np.int32)), _p(out))
+    return out
+
+
+def wonly_forward(X_hat_h, W_tilde_h, bias=None):
+    """-> (y fp64 [T,N], abs_y fp64 [T,N]) for binary16 operands."""
+    X_hat_h = _c(X_hat_h, np.float16)
+    W_tilde_h = _c(W_tilde_h, np.float16)
+    T, K = X_hat_h.shape
+    N = W_tilde_h.shape[0]
+    y = np.empty((T, N), np.float64)
+    a = np.empty((T, N), np.float64)
+    b = None if bias is None else _c(bias, np.float32)
+    lib().orc_wonly_forward(_p(X_hat_h), i64(T), i64(K), i64(K), _p(W_tilde_h), i64(N),
+                            _p(b) if b is not None else None, _p(y), _p(a))
+    return y, a
+
+
 def quant_act(X, inv_s, step_x, zero_x):
     """-> dict(xq int8[T,K], rowsum_x int32[T], colsum_xq int64[K], status)."""
     X = _c(X)

@@ -501,3 +501,62 @@ def test_equalization_reduces_w8a8_error_with_outliers(orc):
         yq = orc.w8a8_output_direct(a["xq"], orc.pack_codes(q["codes_u"], 8), step_x, zero_x, q["step"], q["zero"])
         errs[awe] = np.sqrt(np.mean((yq - y) ** 2))
     assert errs[True] < 0.5 * errs[False]
+
+
+# ------------------------------------------------------------- weight-only forward (binary16)
+
+
+def test_dequant_weight_h_special_cases_and_bound(orc):
+    """Pins of the binary16 W-tilde: (i) a Step that binary16 holds exactly reproduces the binary32
+    Eq. 1 de-quantisation exactly; (ii) a hand-worked value; (iii) in general it is within one
+    binary16 rounding of Step and one of the product of the binary32 one."""
+    rng = np.random.default_rng(3)
+    codes = rng.integers(0, 16, (5, 256)).astype(np.uint8)
+    zero = rng.integers(0, 16, (5, 2)).astype(np.int32)
+    step = np.array([[0.25, 0.0078125]] * 5, np.float32)         # exact in binary16
+    wh = orc.dequant_weight_h(codes, 128, step, zero)
+    w32 = orc.dequant_weight(codes, 128, step, zero)
+    assert np.array_equal(wh.astype(np.float32), w32)
+    # hand-worked: Step = 0.1 -> binary16 0.0999755859375; (13 - 6) * that = 0.6998291015625,
+    # nearest binary16 values are 0.69970703125 and 0.7001953125 -> the first
+    one = orc.dequant_weight_h(np.array([[13]], np.uint8), 0, np.array([0.1], np.float32), np.array([6], np.int32))
+    assert float(one[0, 0]) == 0.69970703125
+    step = rng.uniform(1e-3, 3e-2, (5, 2)).astype(np.float32)
+    wh = orc.dequant_weight_h(codes, 128, step, zero).astype(np.float64)
+    w32 = orc.dequant_weight(codes, 128, step, zero).astype(np.float64)
+    assert np.all(np.abs(wh - w32) <= np.abs(w32) * (2.0 ** -11 + 2.0 ** -11 + 2.0 ** -20))
+    # per-row (group 0) and per-tensor (group -1) parameter indexing
+    s_row, z_row = rng.uniform(1e-3, 3e-2, 5).astype(np.float32), rng.integers(0, 16, 5).astype(np.int32)
+    a = orc.dequant_weight_h(codes, 0, s_row, z_row)
+    for n in range(5):
+        b = orc.dequant_weight_h(codes[n:n + 1], -1, s_row[n:n + 1], z_row[n:n + 1])
+        assert np.array_equal(a[n:n + 1].view(np.uint16), b.view(np.uint16))
+
+
+def test_wonly_forward_reduces_to_matmul(orc):
+    """With binary16 operands the forward is a plain matrix product: equal to numpy's fp64 matmul
+    of the widened operands up to fp64 summation order, to a brute-force loop exactly, and the
+    magnitude output is the product of the absolute values."""
+    rng = np.random.default_rng(4)
+    T, K, N = 7, 96, 5
+    X = rng.standard_normal((T, K)).astype(np.float16)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+    b = rng.standard_normal(N).astype(np.float32)
+    y, a = orc.wonly_forward(X, W, b)
+    ref = X.astype(np.float64) @ W.astype(np.float64).T + b.astype(np.float64)
+    np.testing.assert_allclose(y, ref, rtol=0, atol=1e-12)
+    brute = np.zeros((T, N))
+    for t in range(T):
+        for n in range(N):
+            acc = 0.0
+            for k in range(K):
+                acc += float(X[t, k]) * float(W[n, k])
+            brute[t, n] = acc + float(b[n])
+    assert np.array_equal(y, brute)
+    np.testing.assert_allclose(a, np.abs(X.astype(np.float64)) @ np.abs(W.astype(np.float64)).T + np.abs(b), rtol=1e-13)
+    y0, _ = orc.wonly_forward(X, W)
+    np.testing.assert_allclose(y0 + b, y, rtol=0, atol=1e-12)
+    # a transposed operand or a dropped bias would not survive this: one-hot probes
+    E = np.zeros((1, K), np.float16); E[0, 17] = 1
+    yk, _ = orc.wonly_forward(E, W)
+    assert np.array_equal(yk[0], W[:, 17].astype(np.float64))
