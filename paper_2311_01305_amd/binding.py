@@ -19,7 +19,7 @@ ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD = 1, 2, 4, 8
 
 EXPORTS = ("aweq_workspace_size", "aweq_status_string", "aweq_calib_stats", "aweq_equalize",
            "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock",
-           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8")
+           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8", "aweq_wonly_gemm")
 
 _vp, _i64, _i32, _u64, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_float, C.c_size_t
 
@@ -65,6 +65,8 @@ def load_library():
                                       _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
     lib.aweq_probe_mfma_clock.restype = _i32
     lib.aweq_probe_mfma_clock.argtypes = [_i32, _i32, _vp, _vp]
+    lib.aweq_wonly_gemm.restype = _i32
+    lib.aweq_wonly_gemm.argtypes = [_vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _i64, _vp, _vp, _i32, _i64, _vp, _vp]
     lib.aweq_panel_bytes.restype = _sz
     lib.aweq_panel_bytes.argtypes = [_i64, _i64]
     lib.aweq_pack_panels_i8.restype = _i32
@@ -172,3 +174,10 @@ def aweq_pack_panels_i8(src, rows, K, ld, panels, stream=None):
 
 def aweq_unpack_panels_i8(panels, rows, K, dst, ld, stream=None):
     _check(load_library().aweq_unpack_panels_i8(_ptr(panels), rows, K, _ptr(dst), ld, _stream(stream)))
+
+
+def aweq_wonly_gemm(X_hat, T, K, ldx, codes, bits, group, step_w, zero_w, N, bias, out, out_dt, ldo, status=None,
+                    stream=None):
+    _check(load_library().aweq_wonly_gemm(_ptr(X_hat), T, K, ldx, _ptr(codes), int(bits), int(group), _ptr(step_w),
+                                          _ptr(zero_w), N, _ptr(bias), _ptr(out), out_dt, ldo, _ptr(status),
+                                          _stream(stream)))

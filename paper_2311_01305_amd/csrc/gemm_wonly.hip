@@ -1,0 +1,395 @@
+// Weight-only forward  y[t,n] = sum_k x_hat[t,k] w~[n,k] + b[n]  for the ultra-low-bit setting of
+// Sec. 4.2 (INT4 / INT3 weights per group along K, FP16 activations): the weight codes are
+// de-quantised on the fly (Eq. 1: w~ = Step (u - Z)) into binary16 and multiplied on the matrix
+// cores (v_mfma_f32_32x32x16_f16, fp32 accumulation).
+//
+// MFMA-bound by design.  One workgroup of 8 wavefronts (two per SIMD) owns a 256 (t) x 256 (n)
+// output tile, each wavefront 128 x 64 of it as 4 x 2 MFMA tiles.  A stage is 64 values of K:
+// 256 rows x 128 bytes of activations, brought into LDS by LDS-DMA loads (row-major binary16
+// rows are whole 128-byte lines per stage), and 256 rows x 128 bytes of weights, which every
+// wavefront produces for 32 rows from 16 (INT4) or 12 (INT3) bytes of codes per lane: the codes
+// are widened two at a time into binary16 pairs with the 1024 + u trick (the bit pattern
+// 0x6400 | u is the binary16 number 1024 + u), shifted by 1024 + Z and scaled with packed
+// binary16 arithmetic.  Step is rounded to binary16 first; for |u - Z| <= 2048 the packed
+// product is the correctly rounded binary16 value of (u - Z) Step_h, the value the host-side
+// definition fixes; zero points outside [-1024, 1024] take a binary32 path with the same result.
+// Two 64 KiB stages, double-buffered; the MFMA is issued with the weight fragment first so
+// that a lane ends with four consecutive n of one token (whole-line output stores).
+#include "common.hpp"
+#include <type_traits>
+
+namespace aweq {
+namespace wonly {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 512;
+constexpr int BM = 256, BN = 256;
+constexpr int BKH = 64;              // values of K per stage
+constexpr int kRow = BKH * 2;        // bytes per tile row per stage
+constexpr int kTile = BM * kRow;     // 32 KiB per operand
+constexpr int kStage = 2 * kTile;    // 64 KiB
+constexpr int kLds = 2 * kStage;     // 128 KiB
+constexpr int kXcds = 8;
+
+struct Args {
+    const _Float16* X;     // x_hat [T x K], row-major
+    int64_t ldx;
+    const uint8_t* codes;  // packed codes [N x K], row-major (4 bits: two per byte; 3 bits: bit stream)
+    const float* step;
+    const int32_t* zero;
+    const float* bias;
+    void* out;
+    int64_t ldo;
+    int64_t T, N, K;
+    int group;             // > 0: per group of that many k; 0: per row; -1: per tensor
+    int tiles_m, tiles_n, patch_m, patch_n, patches_n, n_patches;
+};
+
+// chunk swizzle for 128-byte tile rows: rows sharing LDS banks get distinct chunk positions
+// both for 8 and for 16 consecutive rows read at one chunk index
+__device__ __forceinline__ int g8(int r) { return (((r >> 1) & 3) << 1) | (((r >> 3) ^ r) & 1); }
+
+// LDS-DMA load the compiler does not track: lane i's 16 bytes land at lds_addr + 16 i
+__device__ __forceinline__ void dma16(const char* sbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+
+__device__ __forceinline__ f16x2 as_h2(uint32_t u) { return __builtin_bit_cast(f16x2, u); }
+__device__ __forceinline__ uint32_t as_u32(f16x2 h) { return __builtin_bit_cast(uint32_t, h); }
+
+// 32 consecutive codes of one row (the lane's half of a stage row), as loaded
+template <int BITS> struct RawCodes { uint32_t w[BITS == 4 ? 4 : 3]; };
+
+// de-quantise the 8 codes k = 8 d .. 8 d + 7 of the lane's 32 into one 16-byte chunk (natural k order)
+template <int BITS>
+__device__ __forceinline__ v4i dequant8(const RawCodes<BITS>& rc, int d, float step_h, int z, bool fast)
+{
+    uint32_t o[4];
+    if (fast) {
+        const f16x2 zs = as_h2(0x64006400u) + f16x2{(_Float16)z, (_Float16)z};       // 1024 + Z, exact
+        const f16x2 sp = {(_Float16)step_h, (_Float16)step_h};
+        if constexpr (BITS == 4) {
+            // (w >> 4 i) & 0x000f000f holds codes i and i + 4 of the dword in its two halves
+            f16x2 h[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) h[i] = (as_h2(((rc.w[d] >> (4 * i)) & 0x000f000fu) | 0x64006400u) - zs) * sp;
+            o[0] = __builtin_amdgcn_perm(as_u32(h[1]), as_u32(h[0]), 0x05040100u);  // k0 k1
+            o[1] = __builtin_amdgcn_perm(as_u32(h[3]), as_u32(h[2]), 0x05040100u);  // k2 k3
+            o[2] = __builtin_amdgcn_perm(as_u32(h[1]), as_u32(h[0]), 0x07060302u);  // k4 k5
+            o[3] = __builtin_amdgcn_perm(as_u32(h[3]), as_u32(h[2]), 0x07060302u);  // k6 k7
+        } else {
+            // codes 2 j, 2 j + 1 are the 6 bits at bit 6 j of the 96-bit stream
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int j = 4 * d + q, bit = 6 * j, idx = bit >> 5, sh = bit & 31;
+                const uint32_t lo = rc.w[idx], hi = idx + 1 < 3 ? rc.w[idx + 1] : 0u;
+                const uint32_t f = __builtin_amdgcn_alignbit(hi, lo, sh);
+                const uint32_t u2 = ((f & 0x38u) << 13) | ((f & 7u) | 0x64006400u);
+                o[q] = as_u32((as_h2(u2) - zs) * sp);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int c[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int k = 8 * d + 2 * q + e;
+                if constexpr (BITS == 4) c[e] = (int)((rc.w[k >> 3] >> (4 * (k & 7))) & 15u);
+                else {
+                    const int bit = 3 * k, idx = bit >> 5, sh = bit & 31;
+                    const uint32_t lo = rc.w[idx], hi = idx + 1 < 3 ? rc.w[idx + 1] : 0u;
+                    c[e] = (int)(__builtin_amdgcn_alignbit(hi, lo, sh) & 7u);
+                }
+            }
+            const f16x2 h = {(_Float16)((float)(c[0] - z) * step_h), (_Float16)((float)(c[1] - z) * step_h)};
+            o[q] = as_u32(h);
+        }
+    }
+    return v4i{(int)o[0], (int)o[1], (int)o[2], (int)o[3]};
+}
+
+#define SB() __builtin_amdgcn_sched_barrier(0)
+#define MF(A_, B_, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, B_[j]), __builtin_bit_cast(v8h, A_[i]), acc[i][j], 0, 0, 0)
+
+template <int BITS, bool OUT_F16>
+__global__ __launch_bounds__(kThreads) void gemm_wonly_kernel(Args g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int b = blockIdx.x;
+    const int xcd = b % kXcds, seq = b / kXcds;
+    const int per_patch = g.patch_m * g.patch_n;
+    const int patch = (seq / per_patch) * kXcds + xcd;
+    if (patch >= g.n_patches) return;
+    const int within = seq % per_patch;
+    const int pm = patch / g.patches_n, pn = patch % g.patches_n;
+    const int tile_m = pm * g.patch_m + within % g.patch_m;
+    const int tile_n = pn * g.patch_n + within / g.patch_m;
+    if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+
+    // activations, global -> LDS: wave w brings tile rows 32 w .. 32 w + 31, 8 rows x 128 B per
+    // instruction; lane i sits at row i / 8, chunk slot i % 8 and fetches chunk slot ^ g8(row)
+    const char* baseA = reinterpret_cast<const char*>(g.X + m0 * g.ldx);
+    uint32_t oa[4];  // byte offsets from the tile's first row: < 256 * 2 ldx
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = wave * 32 + q * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ g8(row);
+        // rows past the edge re-read the last valid row; their results are never stored
+        const int64_t ra = min(m0 + row, g.T - 1) - m0;
+        oa[q] = (uint32_t)(ra * g.ldx * 2 + chunk * 16);
+    }
+    // weights: wave w produces tile rows 32 w .. 32 w + 31; lane = 2 (row % 32) + half of the stage row
+    const int brow = wave * 32 + (lane >> 1), kpart = lane & 1;
+    const int64_t bn = min(n0 + brow, g.N - 1);
+    const uint8_t* crow = g.codes + bn * (g.K * BITS / 8) + kpart * (32 * BITS / 8);
+    const int64_t pstride = g.group > 0 ? g.K / g.group : 0;
+    const int bsw = g8(brow);
+    const uint32_t ldsB_row = kTile + brow * kRow;
+
+    const int ns = (int)(g.K / BKH);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const uint32_t wave_off = __builtin_amdgcn_readfirstlane(wave) * 4096;
+
+    v16f acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // fragment of K-step qq (16 values = 32 bytes per row): lane reads row lane % 32 of a 32-row
+    // sub-tile, chunk 2 qq + lane / 32
+    const int fr_row = lane & 31, fr_half = lane >> 5;
+    const int fsw = g8(fr_row);
+    int offA[4], offB[4];
+#pragma unroll
+    for (int qq = 0; qq < 4; ++qq) {
+        offA[qq] = (wm * 128 + fr_row) * kRow + ((qq * 2 + fr_half) ^ fsw) * 16;
+        offB[qq] = kTile + (wn * 64 + fr_row) * kRow + ((qq * 2 + fr_half) ^ fsw) * 16;
+    }
+    v4i a0[4], b0[2], a1[4], b1[2];
+
+#define RDA(dst, qq, i) dst[i] = *reinterpret_cast<const v4i*>(st + offA[qq] + (i) * 32 * kRow)
+#define RDB(dst, qq, j) dst[j] = *reinterpret_cast<const v4i*>(st + offB[qq] + (j) * 32 * kRow)
+#define DMA_A(q) dma16(baseA + kload, oa[q], dst_stage + (q) * 1024)
+
+    RawCodes<BITS> rc;
+    float step_h = 0.f;
+    int zq = 0;
+    auto load_codes = [&](int s) {
+        const uint8_t* p = crow + (int64_t)s * (BKH * BITS / 8);
+        if constexpr (BITS == 4) {
+            const v4i w = *reinterpret_cast<const v4i*>(p);
+            rc.w[0] = (uint32_t)w[0]; rc.w[1] = (uint32_t)w[1]; rc.w[2] = (uint32_t)w[2]; rc.w[3] = (uint32_t)w[3];
+        } else {
+            const uint32_t* p32 = reinterpret_cast<const uint32_t*>(p);
+            rc.w[0] = p32[0]; rc.w[1] = p32[1]; rc.w[2] = p32[2];
+        }
+        const int64_t k0 = (int64_t)s * BKH + kpart * 32;
+        const int64_t pi = g.group < 0 ? 0 : (g.group == 0 ? bn : bn * pstride + k0 / g.group);
+        step_h = (float)(_Float16)g.step[pi];   // Step as binary16
+        zq = g.zero[pi];
+    };
+    auto store_weights = [&](int buf) {
+        char* dst = lds + buf * kStage + ldsB_row;
+        const bool fast = zq >= -1024 && zq <= 1024;
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            *reinterpret_cast<v4i*>(dst + (((kpart * 4 + d) ^ bsw) * 16)) = dequant8<BITS>(rc, d, step_h, zq, fast);
+    };
+
+    {
+        const uint32_t dst_stage = lds0 + wave_off;
+        const int64_t kload = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) DMA_A(q);
+        load_codes(0);
+        store_weights(0);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    {
+        const char* st = lds;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) RDA(a0, 0, i);
+        RDB(b0, 0, 0); RDB(b0, 0, 1);
+    }
+
+    // one stage (64 values of K) = four K-steps of 8 MFMAs per wave.  F0 / F1 are the two fragment
+    // register sets; each K-step multiplies one and fetches the other.
+    auto stage = [&](int s, auto has_next_c) {
+        constexpr bool NEXT = decltype(has_next_c)::value;
+        const char* st = lds + (s & 1) * kStage;
+        const uint32_t dst_stage = lds0 + ((s + 1) & 1) * kStage + wave_off;
+        const int64_t kload = (int64_t)(s + 1) * kRow;
+        // K-step 0: multiply F0, fetch F1; the other buffer is free (every wave passed the barrier of
+        // the previous stage), so the next stage starts loading
+        SB();
+        if constexpr (NEXT) load_codes(s + 1);
+        RDA(a1, 1, 0); RDB(b1, 1, 0); RDB(b1, 1, 1); MF(a0, b0, 0, 0);
+        SB();
+        if constexpr (NEXT) DMA_A(0);
+        RDA(a1, 1, 1); RDA(a1, 1, 2); MF(a0, b0, 0, 1);
+        SB();
+        if constexpr (NEXT) DMA_A(1);
+        RDA(a1, 1, 3); MF(a0, b0, 1, 0);
+        SB();
+        if constexpr (NEXT) DMA_A(2);
+        MF(a0, b0, 1, 1);
+        SB();
+        if constexpr (NEXT) DMA_A(3);
+        MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
+        SB();
+        // K-step 1: multiply F1, fetch F0
+        RDA(a0, 2, 0); RDB(b0, 2, 0); RDB(b0, 2, 1); MF(a1, b1, 0, 0);
+        SB();
+        RDA(a0, 2, 1); RDA(a0, 2, 2); MF(a1, b1, 0, 1);
+        SB();
+        RDA(a0, 2, 3); MF(a1, b1, 1, 0);
+        SB();
+        MF(a1, b1, 1, 1); MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+        SB();
+        // K-step 2: multiply F0, fetch F1; the next stage's weights go from codes to LDS here
+        RDA(a1, 3, 0); RDB(b1, 3, 0); RDB(b1, 3, 1); MF(a0, b0, 0, 0);
+        SB();
+        RDA(a1, 3, 1); RDA(a1, 3, 2); MF(a0, b0, 0, 1);
+        SB();
+        RDA(a1, 3, 3); MF(a0, b0, 1, 0);
+        if constexpr (NEXT) store_weights((s + 1) & 1);
+        MF(a0, b0, 1, 1); MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
+        SB();
+        if constexpr (NEXT) {
+            // my share of the next stage has landed, my reads of this stage are done; after the
+            // barrier that holds for every wave
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            SB();
+            st = lds + ((s + 1) & 1) * kStage;
+            // K-step 3: multiply F1, fetch F0 = K-step 0 of the next stage
+            RDA(a0, 0, 0); RDB(b0, 0, 0); RDB(b0, 0, 1); MF(a1, b1, 0, 0);
+            SB();
+            RDA(a0, 0, 1); RDA(a0, 0, 2); MF(a1, b1, 0, 1);
+            SB();
+            RDA(a0, 0, 3); MF(a1, b1, 1, 0);
+            SB();
+            MF(a1, b1, 1, 1); MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+            SB();
+        } else {
+            MF(a1, b1, 0, 0); MF(a1, b1, 0, 1); MF(a1, b1, 1, 0); MF(a1, b1, 1, 1);
+            MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+        }
+    };
+    int s = 0;
+    for (; s + 1 < ns; ++s) stage(s, std::true_type{});
+    stage(s, std::false_type{});
+#undef RDA
+#undef RDB
+#undef DMA_A
+
+    // ---- epilogue.  With the weight fragment as first MFMA operand, register v of lane l in
+    // sub-tile (i, j) is token t = m0 + 128 wm + 32 i + l % 32 and output channel
+    // n = n0 + 64 wn + 32 j + 8 (v / 4) + 4 (l / 32) + v % 4.  Each wave turns its 32 (t) x 64 (n)
+    // slab of sub-tile row i around in a private 8 KiB LDS region (256-byte rows, XOR-swizzled
+    // 16-byte chunks) so that 16 lanes cover one output row of the slab per store.
+    __syncthreads();  // every wave is done with the stage buffers
+    char* slab = lds + wave * 8192;
+    const int wr_t = lane & 31, wr_sw = wr_t & 15, wr_half = lane >> 5;
+    const int rd_r = lane >> 4, rd_c = lane & 15;
+    const int64_t n = n0 + wn * 64 + rd_c * 4;      // this lane's four channels
+    const bool n_ok = n < g.N;                      // N % 4 == 0: all four or none
+    const int64_t t_lane = m0 + wm * 128 + rd_r;    // + 32 i + 4 p
+    v4f bs = {0.f, 0.f, 0.f, 0.f};
+    if (g.bias && n_ok) bs = *reinterpret_cast<const v4f*>(g.bias + n);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v4f o = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                *reinterpret_cast<v4f*>(slab + wr_t * 256 + (((8 * j + 2 * q + wr_half) ^ wr_sw) * 16)) = o;
+            }
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int r = 4 * p + rd_r;
+            v4f o = *reinterpret_cast<const v4f*>(slab + r * 256 + ((rd_c ^ (r & 15)) * 16));
+            const int64_t t = t_lane + i * 32 + 4 * p;
+            if (t < g.T && n_ok) {
+                o += bs;
+                if constexpr (OUT_F16) {
+                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                    h4 oh = {(_Float16)o[0], (_Float16)o[1], (_Float16)o[2], (_Float16)o[3]};
+                    __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out) + t * g.ldo + n));
+                } else {
+                    __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(reinterpret_cast<float*>(g.out) + t * g.ldo + n));
+                }
+            }
+        }
+    }
+}
+#undef SB
+#undef MF
+
+}  // namespace wonly
+}  // namespace aweq
+
+using namespace aweq;
+
+extern "C" int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t ldx,
+                               const void* codes, int bits, int group,
+                               const float* step_w, const int32_t* zero_w, int64_t N,
+                               const float* bias, void* out, aweq_dtype out_dt, int64_t ldo,
+                               uint32_t* status, void* stream)
+{
+    (void)status;
+    if (!X_hat || !codes || !step_w || !zero_w || !out) return AWEQ_ERR_NULL;
+    if (bits != 4 && bits != 3) return AWEQ_ERR_BITS;
+    if (out_dt != AWEQ_F16 && out_dt != AWEQ_F32) return AWEQ_ERR_DTYPE;
+    if (T <= 0 || N <= 0 || K <= 0 || (K % wonly::BKH) != 0 || ldx < K || ldo < N) return AWEQ_ERR_SHAPE;
+    if (K > (1 << 20)) return AWEQ_ERR_SHAPE;  // 32-bit byte offsets inside a tile of activations
+    if (group < -1 || (group > 0 && ((group % wonly::BKH) != 0 || (K % group) != 0))) return AWEQ_ERR_GROUP;
+    if ((N % 4) != 0 || (ldo % 4) != 0) return AWEQ_ERR_SHAPE;
+    if (!aligned16(X_hat) || (ldx % 8) != 0 || !aligned16(codes) || !aligned16(out) || (bias && !aligned16(bias)))
+        return AWEQ_ERR_ALIGN;
+    const int64_t tiles_m = cdiv(T, wonly::BM), tiles_n = cdiv(N, wonly::BN);
+    if (tiles_m * tiles_n > (1ll << 30)) return AWEQ_ERR_SHAPE;
+
+    wonly::Args g;
+    g.X = reinterpret_cast<const _Float16*>(X_hat); g.ldx = ldx;
+    g.codes = reinterpret_cast<const uint8_t*>(codes); g.step = step_w; g.zero = zero_w; g.bias = bias;
+    g.out = out; g.ldo = ldo; g.T = T; g.N = N; g.K = K; g.group = group;
+    g.tiles_m = (int)tiles_m; g.tiles_n = (int)tiles_n;
+    // patch of output tiles an XCD works on at a time: 32 tiles (one per compute unit)
+    g.patch_n = (int)(tiles_n < 4 ? tiles_n : 4);
+    g.patch_m = 32 / g.patch_n;
+    if (g.patch_m > tiles_m) g.patch_m = (int)tiles_m;
+    g.patches_n = (int)cdiv(tiles_n, g.patch_n);
+    const int64_t patches_m = cdiv(tiles_m, g.patch_m);
+    g.n_patches = (int)(patches_m * g.patches_n);
+    const int64_t rounds = cdiv(g.n_patches, wonly::kXcds);
+    const int64_t blocks = rounds * wonly::kXcds * g.patch_m * g.patch_n;
+    if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+
+    const void* fn = nullptr;
+    if (bits == 4) fn = out_dt == AWEQ_F16 ? reinterpret_cast<const void*>(wonly::gemm_wonly_kernel<4, true>)
+                                           : reinterpret_cast<const void*>(wonly::gemm_wonly_kernel<4, false>);
+    else fn = out_dt == AWEQ_F16 ? reinterpret_cast<const void*>(wonly::gemm_wonly_kernel<3, true>)
+                                 : reinterpret_cast<const void*>(wonly::gemm_wonly_kernel<3, false>);
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, wonly::kLds) != hipSuccess) return AWEQ_ERR_LAUNCH;
+    void* args[] = {&g};
+    if (hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(wonly::kThreads), args, wonly::kLds, as_stream(stream)) != hipSuccess)
+        return AWEQ_ERR_LAUNCH;
+    return launch_status();
+}

@@ -185,3 +185,19 @@ def test_panel_layout_helpers(B):
     p = to_panels(m)
     assert p.size == B.aweq_panel_bytes(5, 72) and np.array_equal(from_panels(p, 5, 72), m)
     assert p[64 * 5 + 8] == 0 and p[0:64].tolist() == m[0, :64].tolist() and p[64:128].tolist() == m[1, :64].tolist()
+
+
+def test_wonly_gemm_argument_errors(B):
+    P = 0x10000
+    ok = dict(X_hat=P, T=64, K=128, ldx=128, codes=P, bits=4, group=128, step_w=P, zero_w=P, N=64, bias=None, out=P,
+              out_dt=B.AWEQ_F16, ldo=64, stream=0)
+    call = lambda **kw: B.aweq_wonly_gemm(**{**ok, **kw})
+    assert _code(call, X_hat=None) == "AWEQ_ERR_NULL"
+    assert _code(call, bits=8) == "AWEQ_ERR_BITS"
+    assert _code(call, K=96, ldx=96) == "AWEQ_ERR_SHAPE"          # K % 64
+    assert _code(call, group=32) == "AWEQ_ERR_GROUP"
+    assert _code(call, group=96) == "AWEQ_ERR_GROUP"
+    assert _code(call, N=62, ldo=62) == "AWEQ_ERR_SHAPE"          # N % 4
+    assert _code(call, ldo=32) == "AWEQ_ERR_SHAPE"
+    assert _code(call, out_dt=B.AWEQ_I8) == "AWEQ_ERR_DTYPE"
+    assert _code(call, X_hat=P + 2) == "AWEQ_ERR_ALIGN"
