@@ -19,6 +19,7 @@ if ROOT not in sys.path:
 
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, published
 
 # HBM bytes per GEMM launch, measured with `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
 # on this workload (profiles/gemm_i8_fast_opt6.7b_hbm_traffic.txt), scaled by what the same
@@ -62,10 +63,11 @@ def weight_only_bench(args, torch, B, pipeline, synth, dev):
         X = synth.make_act_torch(seed, T, lin.K, wl, dev)
         W = synth.make_weight_torch(seed, lin.N, lin.K, wl.dtype, dev)
         buf = pipeline.LayerBuffers(T, lin.K, lin.N, torch.float16, bits=bits, group=128, w8a8=False, device=dev)
+        buf.t["y"] = torch.empty((T, lin.N), dtype=torch.float16, device=dev)
         layers.append((lin, X, W, buf))
     torch.cuda.synchronize()
     dt = B.AWEQ_F16
-    stages = ("stats_x", "stats_w", "equalize", "quant_weight", "bias")
+    stages = ("stats_x", "stats_w", "equalize", "quant_weight", "bias", "forward")
 
     def run_layer(lin, X, W, buf, ev=None):
         t, K, N, st = buf.t, lin.K, lin.N, buf.t["status"]
@@ -88,12 +90,17 @@ def weight_only_bench(args, torch, B, pipeline, synth, dev):
         B.aweq_bias_correct(B.BIAS_WEIGHT_ONLY, t["W_hat"], dt, N, K, K, t["mu_xhat"], T, None, None, None, None, None,
                             t["codes"], bits, 128, t["step_w"], t["zero_w"], None, t["delta"], t["bias_out"], 1, None, st)
         mark(5)
+        # the quantised layer's forward with the corrected bias; the synthetic X stands in for the
+        # equalised binary16 activations the preceding block would deliver
+        B.aweq_wonly_gemm(X, T, K, K, t["codes"], bits, 128, t["step_w"], t["zero_w"], N, t["bias_out"], t["y"],
+                          B.AWEQ_F16, N, st)
+        mark(6)
 
     for _ in range(args.warmup):
         for lay in layers:
             run_layer(*lay)
     torch.cuda.synchronize()
-    evs = [[[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in layers] for _ in range(args.steps)]
+    evs = [[[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in layers] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
         for i, lay in enumerate(layers):
@@ -101,31 +108,40 @@ def weight_only_bench(args, torch, B, pipeline, synth, dev):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
-    per_layer, sx_ms, sx_bytes = [], 0.0, 0.0
+    per_layer, sx_ms, sx_bytes, fw_ms, fw_flops, calib_ms = [], 0.0, 0.0, 0.0, 0.0, 0.0
     for i, (lin, *_r) in enumerate(layers):
         ms = {s: sum(evs[k][i][j].elapsed_time(evs[k][i][j + 1]) for k in range(args.steps)) / args.steps
               for j, s in enumerate(stages)}
         sx_ms += ms["stats_x"]
         sx_bytes += 2.0 * T * lin.K
+        fw_ms += ms["forward"]
+        fw_flops += 2.0 * T * lin.N * lin.K
+        calib_ms += sum(v for s, v in ms.items() if s != "forward")
         per_layer.append({"name": lin.name, "N": lin.N, "K": lin.K, "ms": {s: round(v, 4) for s, v in ms.items()},
-                          "stats_x_GBs": round(2.0 * T * lin.K / (ms["stats_x"] * 1e-3) / 1e9, 1)})
+                          "stats_x_GBs": round(2.0 * T * lin.K / (ms["stats_x"] * 1e-3) / 1e9, 1),
+                          "forward_TFLOPs": round(2.0 * T * lin.N * lin.K / (ms["forward"] * 1e-3) / 1e12, 1)})
     status_bits = 0
     for *_r, buf in layers:
         status_bits |= int(buf.t["status"].item())
     achieved = sx_bytes / (sx_ms * 1e-3) / 1e9
+    fw_tflops = fw_flops / (fw_ms * 1e-3) / 1e12
     return {
         "metric": "calibration tokens/sec per layer (stats+equalize+quant+bias); W8A8 GEMM TOPS",
         "value": len(layers) * T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"cfg4 {wl.name}: {len(layers)} linears, T={T} calibration tokens, f16, weight-only "
-                               f"W{bits} per group of 128, fp16 activations, equalization + bias correction; no GEMM in "
-                               "this configuration",
-                   "value_is": "layers * T / step time over statistics, equalization, weight quantizer, bias correction"},
-        "roofline": {"bound": "hbm", "kernel": "col_stats_partial_f16 (+ merge, finalize: the whole aweq_calib_stats call on X)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None,
-                     "note": "achieved = 2 B x T x K of X over the event-timed aweq_calib_stats calls (3 kernels each)"},
+                               f"W{bits} per group of 128, fp16 activations, equalization + bias correction, then "
+                               "the de-quantising fp16 forward GEMM",
+                   "value_is": "layers * T / step time, whole path incl. the weight-only forward"},
+        "calib_tokens_per_s_per_layer_excl_forward": T * len(layers) / (calib_ms * 1e-3),
+        "forward_tflops": fw_tflops,
+        "roofline": {"bound": "mfma", "kernel": f"gemm_wonly_kernel<{bits}, true>", "achieved": fw_tflops,
+                     "peak": F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fw_tflops / F16_PEAK_TFLOPS, "traffic": None,
+                     "note": "achieved = sum 2*T*N*K / sum of event-timed aweq_wonly_gemm launches"},
+        "roofline_stats": {"bound": "hbm", "kernel": "col_stats_partial_f16 (+ merge, finalize: the whole aweq_calib_stats call on X)",
+                           "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                           "note": "achieved = 2 B x T x K of X over the event-timed aweq_calib_stats calls (3 kernels each)"},
         "layers": per_layer, "status_bits": status_bits,
     }
 
