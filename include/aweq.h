@@ -58,7 +58,8 @@ typedef enum {
     AWEQ_OP_EQUALIZE = 1,
     AWEQ_OP_QUANT_WEIGHT = 2,
     AWEQ_OP_W8A8_GEMM = 3,
-    AWEQ_OP_BIAS_CORRECT = 4
+    AWEQ_OP_BIAS_CORRECT = 4,
+    AWEQ_OP_WONLY_GEMM = 5
 } aweq_op;
 
 enum { AWEQ_BIAS_W8A8 = 0, AWEQ_BIAS_WEIGHT_ONLY = 1 };
@@ -188,16 +189,17 @@ int aweq_bias_correct(int mode, const void* W_hat, aweq_dtype dt, int64_t N, int
  * y[t,n] = sum_k x_hat[t,k] w~[n,k] + bias[n], w~ = Step (u - Z) the de-quantised weight of Eq. 1.
  * X_hat[T x K]: binary16 equalised activations, row-major, pitch ldx (the caller has folded
  * diag(s)^-1 into what produces them, Eq. 3); codes / step_w / zero_w: what aweq_quant_weight wrote
- * for bits in {4, 3} and the same group (group > 0: a multiple of 64 dividing K; 0: per row; -1: per
+ * for bits in {4, 3} and the same group (group > 0: a multiple of 32 dividing K; 0: per row; -1: per
  * tensor); bias[N] fp32 nullable; out[T x N] F16 or F32, pitch ldo.  K % 64 == 0, N % 4 == 0,
  * ldo % 4 == 0, 16-byte aligned pointers.  Arithmetic: the weight operand is binary16,
- * w~_h = RN16((u - Z) * RN16(Step)); products are exact in fp32 and accumulated in fp32 on the matrix
- * cores (summation order unspecified). */
+ * w~_h = RN16((u - Z) * RN16(Step)), written once per call into the workspace (N * K * 2 bytes:
+ * aweq_workspace_size(AWEQ_OP_WONLY_GEMM, T, K, N)); products are exact in fp32 and accumulated in
+ * fp32 on the matrix cores (summation order unspecified). */
 int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t ldx,
                     const void* codes, int bits, int group,
                     const float* step_w, const int32_t* zero_w, int64_t N,
                     const float* bias, void* out, aweq_dtype out_dt, int64_t ldo,
-                    uint32_t* status, void* stream);
+                    void* ws, size_t ws_bytes, uint32_t* status, void* stream);
 
 /* ---- Diagnostic (not a stage of the method; for measurement reports).  One workgroup of four
  * wavefronts per compute unit issues iters x 16 back-to-back independent int8 32x32x32 MFMAs with

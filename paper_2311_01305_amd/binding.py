@@ -13,7 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "libaweq.so")
 _lib = None
 
 AWEQ_F32, AWEQ_F16, AWEQ_I8 = 0, 1, 2
-OP_CALIB_STATS, OP_EQUALIZE, OP_QUANT_WEIGHT, OP_W8A8_GEMM, OP_BIAS_CORRECT = 0, 1, 2, 3, 4
+OP_CALIB_STATS, OP_EQUALIZE, OP_QUANT_WEIGHT, OP_W8A8_GEMM, OP_BIAS_CORRECT, OP_WONLY_GEMM = 0, 1, 2, 3, 4, 5
 BIAS_W8A8, BIAS_WEIGHT_ONLY = 0, 1
 ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD = 1, 2, 4, 8
 
@@ -66,7 +66,8 @@ def load_library():
     lib.aweq_probe_mfma_clock.restype = _i32
     lib.aweq_probe_mfma_clock.argtypes = [_i32, _i32, _vp, _vp]
     lib.aweq_wonly_gemm.restype = _i32
-    lib.aweq_wonly_gemm.argtypes = [_vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _i64, _vp, _vp, _i32, _i64, _vp, _vp]
+    lib.aweq_wonly_gemm.argtypes = [_vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _i64, _vp, _vp, _i32, _i64, _vp, _sz,
+                                    _vp, _vp]
     lib.aweq_panel_bytes.restype = _sz
     lib.aweq_panel_bytes.argtypes = [_i64, _i64]
     lib.aweq_pack_panels_i8.restype = _i32
@@ -176,8 +177,9 @@ def aweq_unpack_panels_i8(panels, rows, K, dst, ld, stream=None):
     _check(load_library().aweq_unpack_panels_i8(_ptr(panels), rows, K, _ptr(dst), ld, _stream(stream)))
 
 
-def aweq_wonly_gemm(X_hat, T, K, ldx, codes, bits, group, step_w, zero_w, N, bias, out, out_dt, ldo, status=None,
-                    stream=None):
+def aweq_wonly_gemm(X_hat, T, K, ldx, codes, bits, group, step_w, zero_w, N, bias, out, out_dt, ldo, ws,
+                    status=None, stream=None, ws_bytes=None):
     _check(load_library().aweq_wonly_gemm(_ptr(X_hat), T, K, ldx, _ptr(codes), int(bits), int(group), _ptr(step_w),
-                                          _ptr(zero_w), N, _ptr(bias), _ptr(out), out_dt, ldo, _ptr(status),
+                                          _ptr(zero_w), N, _ptr(bias), _ptr(out), out_dt, ldo, _ptr(ws),
+                                          _nbytes(ws) if ws_bytes is None else ws_bytes, _ptr(status),
                                           _stream(stream)))

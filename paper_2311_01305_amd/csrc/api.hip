@@ -7,11 +7,11 @@ size_t stats_ws_bytes_export(int64_t rows, int64_t K);
 
 extern "C" size_t aweq_workspace_size(aweq_op op, int64_t rows, int64_t K, int64_t N)
 {
-    (void)N;
     if (rows <= 0 || K <= 0) return 0;
     switch (op) {
     case AWEQ_OP_CALIB_STATS: return aweq::stats_ws_bytes_export(rows, K);
     case AWEQ_OP_QUANT_WEIGHT: return 16;  // tensor-wide extremes for group = -1
+    case AWEQ_OP_WONLY_GEMM: return N > 0 ? (size_t)N * (size_t)K * 2 : 0;  // the binary16 weight
     case AWEQ_OP_EQUALIZE:
     case AWEQ_OP_W8A8_GEMM:
     case AWEQ_OP_BIAS_CORRECT:

@@ -1,20 +1,26 @@
 // Weight-only forward  y[t,n] = sum_k x_hat[t,k] w~[n,k] + b[n]  for the ultra-low-bit setting of
 // Sec. 4.2 (INT4 / INT3 weights per group along K, FP16 activations): the weight codes are
-// de-quantised on the fly (Eq. 1: w~ = Step (u - Z)) into binary16 and multiplied on the matrix
-// cores (v_mfma_f32_32x32x16_f16, fp32 accumulation).
+// de-quantised (Eq. 1: w~ = Step (u - Z)) into binary16 and multiplied on the matrix cores
+// (v_mfma_f32_32x32x16_f16, fp32 accumulation).
 //
-// MFMA-bound by design.  One workgroup of 8 wavefronts (two per SIMD) owns a 256 (t) x 256 (n)
-// output tile, each wavefront 128 x 64 of it as 4 x 2 MFMA tiles.  A stage is 64 values of K:
-// 256 rows x 128 bytes of activations, brought into LDS by LDS-DMA loads (row-major binary16
-// rows are whole 128-byte lines per stage), and 256 rows x 128 bytes of weights, which every
-// wavefront produces for 32 rows from 16 (INT4) or 12 (INT3) bytes of codes per lane: the codes
-// are widened two at a time into binary16 pairs with the 1024 + u trick (the bit pattern
-// 0x6400 | u is the binary16 number 1024 + u), shifted by 1024 + Z and scaled with packed
-// binary16 arithmetic.  Step is rounded to binary16 first; for |u - Z| <= 2048 the packed
-// product is the correctly rounded binary16 value of (u - Z) Step_h, the value the host-side
-// definition fixes; zero points outside [-1024, 1024] take a binary32 path with the same result.
-// Two 64 KiB stages, double-buffered; the MFMA is issued with the weight fragment first so
-// that a lane ends with four consecutive n of one token (whole-line output stores).
+// Two kernels.  dequant_weight_h_kernel writes the binary16 weight [N x K] once per call into
+// the caller's workspace: at calibration sizes (hundreds of thousands of tokens) that pass is
+// noise, while de-quantising inside the GEMM costs every row tile of tokens the same VALU work
+// again (measured: a third of the GEMM's time).  A lane widens two codes at a time into
+// binary16 with the 1024 + u trick (the bit pattern 0x6400 | u is the binary16 number
+// 1024 + u), subtracts 1024 + Z and multiplies by Step with packed binary16 arithmetic.  Step
+// is rounded to binary16 first; for |u - Z| <= 2048 the packed product is the correctly
+// rounded binary16 value of (u - Z) Step_h, the value the host-side definition fixes; zero
+// points outside [-1024, 1024] take a binary32 path with the same result.
+// gemm_f16_kernel: one workgroup of 8 wavefronts (two per SIMD) owns a 256 (t) x 256 (n) output
+// tile, each wavefront 128 x 64 of it as 4 x 2 MFMA tiles.  A stage is 64 values of K = 128 bytes
+// per row (whole cache lines of both row-major operands), brought in by LDS-DMA loads the
+// compiler does not track.  The activation half of a stage goes through a ring of three
+// 32 KiB slots (two stages ahead: it misses the L2 twice as often as the weight half and its
+// round trip does not fit in one stage), the weight half through two slots; with the
+// wavefront's loads retiring in issue order, "at most the 4 newest outstanding" at the end of a
+// stage means everything the next stage reads has landed.  The MFMA is issued with the weight
+// fragment first so that a lane ends with four consecutive n of one token.
 #include "common.hpp"
 #include <type_traits>
 
@@ -31,21 +37,19 @@ constexpr int BM = 256, BN = 256;
 constexpr int BKH = 64;              // values of K per stage
 constexpr int kRow = BKH * 2;        // bytes per tile row per stage
 constexpr int kTile = BM * kRow;     // 32 KiB per operand
-constexpr int kStage = 2 * kTile;    // 64 KiB
-constexpr int kLds = 2 * kStage;     // 128 KiB
+constexpr int kSlotsA = 3;
+constexpr int kLdsB = kSlotsA * kTile;          // weight slots start behind the activation ring
+constexpr int kLds = kSlotsA * kTile + 2 * kTile;  // 160 KiB
 constexpr int kXcds = 8;
 
 struct Args {
     const _Float16* X;     // x_hat [T x K], row-major
     int64_t ldx;
-    const uint8_t* codes;  // packed codes [N x K], row-major (4 bits: two per byte; 3 bits: bit stream)
-    const float* step;
-    const int32_t* zero;
+    const _Float16* W;     // de-quantised weight [N x K], row-major (the workspace)
     const float* bias;
     void* out;
     int64_t ldo;
     int64_t T, N, K;
-    int group;             // > 0: per group of that many k; 0: per row; -1: per tensor
     int tiles_m, tiles_n, patch_m, patch_n, patches_n, n_patches;
 };
 
@@ -114,11 +118,44 @@ __device__ __forceinline__ v4i dequant8(const RawCodes<BITS>& rc, int d, float s
     return v4i{(int)o[0], (int)o[1], (int)o[2], (int)o[3]};
 }
 
+// one thread per 32 consecutive codes of a row: 16 (INT4) or 12 (INT3) bytes in, 64 bytes out
+template <int BITS>
+__global__ __launch_bounds__(256) void dequant_weight_h_kernel(
+    const uint8_t* __restrict__ codes, int64_t N, int64_t K, int group, const float* __restrict__ step,
+    const int32_t* __restrict__ zero, _Float16* __restrict__ W)
+{
+    const int64_t per_row = K / 32;
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= N * per_row) return;
+    const int64_t n = id / per_row, kk = id % per_row;
+    const uint8_t* p = codes + n * (K * BITS / 8) + kk * (32 * BITS / 8);
+    RawCodes<BITS> rc;
+    if constexpr (BITS == 4) {
+        const v4i w = *reinterpret_cast<const v4i*>(p);
+        rc.w[0] = (uint32_t)w[0]; rc.w[1] = (uint32_t)w[1]; rc.w[2] = (uint32_t)w[2]; rc.w[3] = (uint32_t)w[3];
+    } else {
+        const uint32_t* p32 = reinterpret_cast<const uint32_t*>(p);
+        rc.w[0] = p32[0]; rc.w[1] = p32[1]; rc.w[2] = p32[2];
+    }
+    const int64_t pi = group < 0 ? 0 : (group == 0 ? n : n * (K / group) + (kk * 32) / group);
+    const float step_h = (float)(_Float16)step[pi];   // Step as binary16
+    const int z = zero[pi];
+    const bool fast = z >= -1024 && z <= 1024;
+    v4i* dst = reinterpret_cast<v4i*>(W + n * K + kk * 32);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) dst[d] = dequant8<BITS>(rc, d, step_h, z, fast);
+}
+
 #define SB() __builtin_amdgcn_sched_barrier(0)
 #define MF(A_, B_, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, B_[j]), __builtin_bit_cast(v8h, A_[i]), acc[i][j], 0, 0, 0)
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
-template <int BITS, bool OUT_F16>
-__global__ __launch_bounds__(kThreads) void gemm_wonly_kernel(Args g)
+template <bool OUT_F16>
+__global__ __launch_bounds__(kThreads) void gemm_f16_kernel(Args g)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -135,26 +172,20 @@ __global__ __launch_bounds__(kThreads) void gemm_wonly_kernel(Args g)
     if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
 
-    // activations, global -> LDS: wave w brings tile rows 32 w .. 32 w + 31, 8 rows x 128 B per
+    // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 8 rows x 128 B per
     // instruction; lane i sits at row i / 8, chunk slot i % 8 and fetches chunk slot ^ g8(row)
     const char* baseA = reinterpret_cast<const char*>(g.X + m0 * g.ldx);
-    uint32_t oa[4];  // byte offsets from the tile's first row: < 256 * 2 ldx
+    const char* baseB = reinterpret_cast<const char*>(g.W + n0 * g.K);
+    uint32_t oa[4], ob[4];  // byte offsets from the tile's first row: < 256 * 2 ldx
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int row = wave * 32 + q * 8 + (lane >> 3);
         const int chunk = (lane & 7) ^ g8(row);
         // rows past the edge re-read the last valid row; their results are never stored
-        const int64_t ra = min(m0 + row, g.T - 1) - m0;
+        const int64_t ra = min(m0 + row, g.T - 1) - m0, rb = min(n0 + row, g.N - 1) - n0;
         oa[q] = (uint32_t)(ra * g.ldx * 2 + chunk * 16);
+        ob[q] = (uint32_t)(rb * g.K * 2 + chunk * 16);
     }
-    // weights: wave w produces tile rows 32 w .. 32 w + 31; lane = 2 (row % 32) + half of the stage row
-    const int brow = wave * 32 + (lane >> 1), kpart = lane & 1;
-    const int64_t bn = min(n0 + brow, g.N - 1);
-    const uint8_t* crow = g.codes + bn * (g.K * BITS / 8) + kpart * (32 * BITS / 8);
-    const int64_t pstride = g.group > 0 ? g.K / g.group : 0;
-    const int bsw = g8(brow);
-    const uint32_t ldsB_row = kTile + brow * kRow;
-
     const int ns = (int)(g.K / BKH);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
     const uint32_t wave_off = __builtin_amdgcn_readfirstlane(wave) * 4096;
@@ -175,108 +206,95 @@ __global__ __launch_bounds__(kThreads) void gemm_wonly_kernel(Args g)
 #pragma unroll
     for (int qq = 0; qq < 4; ++qq) {
         offA[qq] = (wm * 128 + fr_row) * kRow + ((qq * 2 + fr_half) ^ fsw) * 16;
-        offB[qq] = kTile + (wn * 64 + fr_row) * kRow + ((qq * 2 + fr_half) ^ fsw) * 16;
+        offB[qq] = kLdsB + (wn * 64 + fr_row) * kRow + ((qq * 2 + fr_half) ^ fsw) * 16;
     }
     v4i a0[4], b0[2], a1[4], b1[2];
 
-#define RDA(dst, qq, i) dst[i] = *reinterpret_cast<const v4i*>(st + offA[qq] + (i) * 32 * kRow)
-#define RDB(dst, qq, j) dst[j] = *reinterpret_cast<const v4i*>(st + offB[qq] + (j) * 32 * kRow)
-#define DMA_A(q) dma16(baseA + kload, oa[q], dst_stage + (q) * 1024)
+#define RDA(dst, qq, i) dst[i] = *reinterpret_cast<const v4i*>(sa + offA[qq] + (i) * 32 * kRow)
+#define RDB(dst, qq, j) dst[j] = *reinterpret_cast<const v4i*>(sb + offB[qq] + (j) * 32 * kRow)
+#define DMA_A(q, s_) dma16(baseA + (int64_t)(s_) * kRow, oa[q], lds0 + ((s_) % kSlotsA) * kTile + wave_off + (q) * 1024)
+#define DMA_B(q, s_) dma16(baseB + (int64_t)(s_) * kRow, ob[q], lds0 + kLdsB + ((s_) & 1) * kTile + wave_off + (q) * 1024)
 
-    RawCodes<BITS> rc;
-    float step_h = 0.f;
-    int zq = 0;
-    auto load_codes = [&](int s) {
-        const uint8_t* p = crow + (int64_t)s * (BKH * BITS / 8);
-        if constexpr (BITS == 4) {
-            const v4i w = *reinterpret_cast<const v4i*>(p);
-            rc.w[0] = (uint32_t)w[0]; rc.w[1] = (uint32_t)w[1]; rc.w[2] = (uint32_t)w[2]; rc.w[3] = (uint32_t)w[3];
-        } else {
-            const uint32_t* p32 = reinterpret_cast<const uint32_t*>(p);
-            rc.w[0] = p32[0]; rc.w[1] = p32[1]; rc.w[2] = p32[2];
-        }
-        const int64_t k0 = (int64_t)s * BKH + kpart * 32;
-        const int64_t pi = g.group < 0 ? 0 : (g.group == 0 ? bn : bn * pstride + k0 / g.group);
-        step_h = (float)(_Float16)g.step[pi];   // Step as binary16
-        zq = g.zero[pi];
-    };
-    auto store_weights = [&](int buf) {
-        char* dst = lds + buf * kStage + ldsB_row;
-        const bool fast = zq >= -1024 && zq <= 1024;
+    // prologue: stage 0 of both operands, stage 1 of the activations
 #pragma unroll
-        for (int d = 0; d < 4; ++d)
-            *reinterpret_cast<v4i*>(dst + (((kpart * 4 + d) ^ bsw) * 16)) = dequant8<BITS>(rc, d, step_h, zq, fast);
-    };
-
-    {
-        const uint32_t dst_stage = lds0 + wave_off;
-        const int64_t kload = 0;
+    for (int q = 0; q < 4; ++q) DMA_A(q, 0);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) DMA_A(q);
-        load_codes(0);
-        store_weights(0);
+    for (int q = 0; q < 4; ++q) DMA_B(q, 0);
+    if (ns > 1) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) DMA_A(q, 1);
+        wait_vm<4>();
+    } else {
+        wait_vm<0>();
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     {
-        const char* st = lds;
+        const char* sa = lds;
+        const char* sb = lds;
 #pragma unroll
         for (int i = 0; i < 4; ++i) RDA(a0, 0, i);
         RDB(b0, 0, 0); RDB(b0, 0, 1);
     }
 
     // one stage (64 values of K) = four K-steps of 8 MFMAs per wave.  F0 / F1 are the two fragment
-    // register sets; each K-step multiplies one and fetches the other.
-    auto stage = [&](int s, auto has_next_c) {
-        constexpr bool NEXT = decltype(has_next_c)::value;
-        const char* st = lds + (s & 1) * kStage;
-        const uint32_t dst_stage = lds0 + ((s + 1) & 1) * kStage + wave_off;
-        const int64_t kload = (int64_t)(s + 1) * kRow;
-        // K-step 0: multiply F0, fetch F1; the other buffer is free (every wave passed the barrier of
-        // the previous stage), so the next stage starts loading
+    // register sets; each K-step multiplies one and fetches the other.  NEXT: there is a stage
+    // s + 1 (its weights are requested here); NEXT2: there is a stage s + 2 (its activations are).
+    auto stage = [&](int s, auto next_c, auto next2_c) {
+        constexpr bool NEXT = decltype(next_c)::value;
+        constexpr bool NEXT2 = decltype(next2_c)::value;
+        const char* sa = lds + (s % kSlotsA) * kTile;
+        const char* sb = lds + (s & 1) * kTile;
+        // K-step 0: multiply F0, fetch F1.  The slots of stage s - 1 are free (every wave passed that
+        // stage's barrier): the weights of stage s + 1 and the activations of stage s + 2 go there
         SB();
-        if constexpr (NEXT) load_codes(s + 1);
         RDA(a1, 1, 0); RDB(b1, 1, 0); RDB(b1, 1, 1); MF(a0, b0, 0, 0);
         SB();
-        if constexpr (NEXT) DMA_A(0);
+        if constexpr (NEXT) DMA_B(0, s + 1);
         RDA(a1, 1, 1); RDA(a1, 1, 2); MF(a0, b0, 0, 1);
         SB();
-        if constexpr (NEXT) DMA_A(1);
+        if constexpr (NEXT) DMA_B(1, s + 1);
         RDA(a1, 1, 3); MF(a0, b0, 1, 0);
         SB();
-        if constexpr (NEXT) DMA_A(2);
+        if constexpr (NEXT) DMA_B(2, s + 1);
         MF(a0, b0, 1, 1);
         SB();
-        if constexpr (NEXT) DMA_A(3);
+        if constexpr (NEXT) DMA_B(3, s + 1);
         MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
         SB();
         // K-step 1: multiply F1, fetch F0
         RDA(a0, 2, 0); RDB(b0, 2, 0); RDB(b0, 2, 1); MF(a1, b1, 0, 0);
         SB();
+        if constexpr (NEXT2) DMA_A(0, s + 2);
         RDA(a0, 2, 1); RDA(a0, 2, 2); MF(a1, b1, 0, 1);
         SB();
+        if constexpr (NEXT2) DMA_A(1, s + 2);
         RDA(a0, 2, 3); MF(a1, b1, 1, 0);
         SB();
-        MF(a1, b1, 1, 1); MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+        if constexpr (NEXT2) DMA_A(2, s + 2);
+        MF(a1, b1, 1, 1);
         SB();
-        // K-step 2: multiply F0, fetch F1; the next stage's weights go from codes to LDS here
+        if constexpr (NEXT2) DMA_A(3, s + 2);
+        MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+        SB();
+        // K-step 2: multiply F0, fetch F1
         RDA(a1, 3, 0); RDB(b1, 3, 0); RDB(b1, 3, 1); MF(a0, b0, 0, 0);
         SB();
         RDA(a1, 3, 1); RDA(a1, 3, 2); MF(a0, b0, 0, 1);
         SB();
         RDA(a1, 3, 3); MF(a0, b0, 1, 0);
-        if constexpr (NEXT) store_weights((s + 1) & 1);
+        SB();
         MF(a0, b0, 1, 1); MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
         SB();
         if constexpr (NEXT) {
-            // my share of the next stage has landed, my reads of this stage are done; after the
-            // barrier that holds for every wave
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // stage s + 1 has landed for this wave (only the 4 newest loads, the activations of stage
+            // s + 2, may still be out), its reads of stage s are done; after the barrier that holds
+            // for every wave
+            if constexpr (NEXT2) wait_vm<4>(); else wait_vm<0>();
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
             SB();
-            st = lds + ((s + 1) & 1) * kStage;
+            sa = lds + ((s + 1) % kSlotsA) * kTile;
+            sb = lds + ((s + 1) & 1) * kTile;
             // K-step 3: multiply F1, fetch F0 = K-step 0 of the next stage
             RDA(a0, 0, 0); RDB(b0, 0, 0); RDB(b0, 0, 1); MF(a1, b1, 0, 0);
             SB();
@@ -292,11 +310,13 @@ __global__ __launch_bounds__(kThreads) void gemm_wonly_kernel(Args g)
         }
     };
     int s = 0;
-    for (; s + 1 < ns; ++s) stage(s, std::true_type{});
-    stage(s, std::false_type{});
+    for (; s + 2 < ns; ++s) stage(s, std::true_type{}, std::true_type{});
+    if (s + 1 < ns) { stage(s, std::true_type{}, std::false_type{}); ++s; }
+    stage(s, std::false_type{}, std::false_type{});
 #undef RDA
 #undef RDB
 #undef DMA_A
+#undef DMA_B
 
     // ---- epilogue.  With the weight fragment as first MFMA operand, register v of lane l in
     // sub-tile (i, j) is token t = m0 + 128 wm + 32 i + l % 32 and output channel
@@ -351,25 +371,36 @@ extern "C" int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t 
                                const void* codes, int bits, int group,
                                const float* step_w, const int32_t* zero_w, int64_t N,
                                const float* bias, void* out, aweq_dtype out_dt, int64_t ldo,
-                               uint32_t* status, void* stream)
+                               void* ws, size_t ws_bytes, uint32_t* status, void* stream)
 {
     (void)status;
     if (!X_hat || !codes || !step_w || !zero_w || !out) return AWEQ_ERR_NULL;
     if (bits != 4 && bits != 3) return AWEQ_ERR_BITS;
     if (out_dt != AWEQ_F16 && out_dt != AWEQ_F32) return AWEQ_ERR_DTYPE;
     if (T <= 0 || N <= 0 || K <= 0 || (K % wonly::BKH) != 0 || ldx < K || ldo < N) return AWEQ_ERR_SHAPE;
-    if (K > (1 << 20)) return AWEQ_ERR_SHAPE;  // 32-bit byte offsets inside a tile of activations
-    if (group < -1 || (group > 0 && ((group % wonly::BKH) != 0 || (K % group) != 0))) return AWEQ_ERR_GROUP;
+    if (K > (1 << 20)) return AWEQ_ERR_SHAPE;  // 32-bit byte offsets inside a tile of rows
+    if (group < -1 || (group > 0 && ((group % 32) != 0 || (K % group) != 0))) return AWEQ_ERR_GROUP;
     if ((N % 4) != 0 || (ldo % 4) != 0) return AWEQ_ERR_SHAPE;
     if (!aligned16(X_hat) || (ldx % 8) != 0 || !aligned16(codes) || !aligned16(out) || (bias && !aligned16(bias)))
         return AWEQ_ERR_ALIGN;
+    if (!ws || ws_bytes < (size_t)N * (size_t)K * 2) return AWEQ_ERR_WORKSPACE;
+    if (!aligned16(ws)) return AWEQ_ERR_ALIGN;
     const int64_t tiles_m = cdiv(T, wonly::BM), tiles_n = cdiv(N, wonly::BN);
     if (tiles_m * tiles_n > (1ll << 30)) return AWEQ_ERR_SHAPE;
+    hipStream_t st = as_stream(stream);
+
+    // the binary16 weight, once
+    _Float16* W = reinterpret_cast<_Float16*>(ws);
+    const int64_t dq_blocks = cdiv(N * (K / 32), 256);
+    if (dq_blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+    const uint8_t* cb = reinterpret_cast<const uint8_t*>(codes);
+    if (bits == 4) wonly::dequant_weight_h_kernel<4><<<(unsigned)dq_blocks, 256, 0, st>>>(cb, N, K, group, step_w, zero_w, W);
+    else wonly::dequant_weight_h_kernel<3><<<(unsigned)dq_blocks, 256, 0, st>>>(cb, N, K, group, step_w, zero_w, W);
 
     wonly::Args g;
     g.X = reinterpret_cast<const _Float16*>(X_hat); g.ldx = ldx;
-    g.codes = reinterpret_cast<const uint8_t*>(codes); g.step = step_w; g.zero = zero_w; g.bias = bias;
-    g.out = out; g.ldo = ldo; g.T = T; g.N = N; g.K = K; g.group = group;
+    g.W = W; g.bias = bias;
+    g.out = out; g.ldo = ldo; g.T = T; g.N = N; g.K = K;
     g.tiles_m = (int)tiles_m; g.tiles_n = (int)tiles_n;
     // patch of output tiles an XCD works on at a time: 32 tiles (one per compute unit)
     g.patch_n = (int)(tiles_n < 4 ? tiles_n : 4);
@@ -382,14 +413,11 @@ extern "C" int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t 
     const int64_t blocks = rounds * wonly::kXcds * g.patch_m * g.patch_n;
     if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
 
-    const void* fn = nullptr;
-    if (bits == 4) fn = out_dt == AWEQ_F16 ? reinterpret_cast<const void*>(wonly::gemm_wonly_kernel<4, true>)
-                                           : reinterpret_cast<const void*>(wonly::gemm_wonly_kernel<4, false>);
-    else fn = out_dt == AWEQ_F16 ? reinterpret_cast<const void*>(wonly::gemm_wonly_kernel<3, true>)
-                                 : reinterpret_cast<const void*>(wonly::gemm_wonly_kernel<3, false>);
+    const void* fn = out_dt == AWEQ_F16 ? reinterpret_cast<const void*>(wonly::gemm_f16_kernel<true>)
+                                        : reinterpret_cast<const void*>(wonly::gemm_f16_kernel<false>);
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, wonly::kLds) != hipSuccess) return AWEQ_ERR_LAUNCH;
     void* args[] = {&g};
-    if (hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(wonly::kThreads), args, wonly::kLds, as_stream(stream)) != hipSuccess)
+    if (hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(wonly::kThreads), args, wonly::kLds, st) != hipSuccess)
         return AWEQ_ERR_LAUNCH;
     return launch_status();
 }

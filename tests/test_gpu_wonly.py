@@ -44,13 +44,14 @@ def make_weights(orc, rng, N, K, bits, group, shift=0.0):
 def run(B, Xh, packed, q, bits, group, N, bias, odt):
     T, K = Xh.shape
     out = torch.full((T, N), 7.0, dtype=torch.float16 if odt == np.float16 else torch.float32, device=DEV)
+    ws = torch.empty(B.aweq_workspace_size(B.OP_WONLY_GEMM, T, K, N), dtype=torch.uint8, device=DEV)
     B.aweq_wonly_gemm(dev(Xh), T, K, K, dev(packed), bits, group, dev(q["step"].reshape(-1)), dev(q["zero"].reshape(-1)),
-                      N, dev(bias) if bias is not None else None, out, B.AWEQ_F16 if odt == np.float16 else B.AWEQ_F32, N)
+                      N, dev(bias) if bias is not None else None, out, B.AWEQ_F16 if odt == np.float16 else B.AWEQ_F32, N, ws)
     return host(out)
 
 
 @pytest.mark.parametrize("bits", [4, 3])
-@pytest.mark.parametrize("N,K,group", [(260, 256, 128), (64, 128, 64), (36, 512, 0), (40, 192, -1), (300, 1024, 512)])
+@pytest.mark.parametrize("N,K,group", [(260, 256, 128), (64, 128, 64), (68, 96 + 32, 32), (36, 512, 0), (40, 192, -1), (300, 1024, 512)])
 def test_dequantised_weight_bit_exact_through_one_hot_rows(B, orc, bits, N, K, group):
     progress(f"one-hot W{bits} N={N} K={K} g={group}")
     rng = np.random.default_rng(bits * 1000 + N + K)

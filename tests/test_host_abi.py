@@ -190,12 +190,15 @@ def test_panel_layout_helpers(B):
 def test_wonly_gemm_argument_errors(B):
     P = 0x10000
     ok = dict(X_hat=P, T=64, K=128, ldx=128, codes=P, bits=4, group=128, step_w=P, zero_w=P, N=64, bias=None, out=P,
-              out_dt=B.AWEQ_F16, ldo=64, stream=0)
+              out_dt=B.AWEQ_F16, ldo=64, ws=P, ws_bytes=64 * 128 * 2, stream=0)
+    assert B.aweq_workspace_size(B.OP_WONLY_GEMM, 64, 128, 64) == 64 * 128 * 2
     call = lambda **kw: B.aweq_wonly_gemm(**{**ok, **kw})
+    assert _code(call, ws=None, ws_bytes=0) == "AWEQ_ERR_WORKSPACE"
+    assert _code(call, ws_bytes=100) == "AWEQ_ERR_WORKSPACE"
     assert _code(call, X_hat=None) == "AWEQ_ERR_NULL"
     assert _code(call, bits=8) == "AWEQ_ERR_BITS"
     assert _code(call, K=96, ldx=96) == "AWEQ_ERR_SHAPE"          # K % 64
-    assert _code(call, group=32) == "AWEQ_ERR_GROUP"
+    assert _code(call, group=16) == "AWEQ_ERR_GROUP"
     assert _code(call, group=96) == "AWEQ_ERR_GROUP"
     assert _code(call, N=62, ldo=62) == "AWEQ_ERR_SHAPE"          # N % 4
     assert _code(call, ldo=32) == "AWEQ_ERR_SHAPE"
