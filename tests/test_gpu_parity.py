@@ -385,6 +385,9 @@ def gpu_gemm(B, xq, wq, want_i32=True, deq=None, colsum=True):
     (300, 260, 328),     # K % 64 = 8
     (300, 202, 256),     # N % 4 != 0: falls back to the generic kernel
     (300, 203, 200),     # generic kernel, zero-filled last panel
+    (5157, 4100, 512),   # 21 x 17 = 357 tiles on 256 persistent workgroups: second tiles, ragged edges on
+                         # both sides, the relaxed wait after interior tiles and the full wait after edge tiles
+    (5157, 4100, 320),   # the same with five panels (never relaxed)
 ])
 def test_gemm_parity(B, orc, T, N, K):
     progress(f"gemm T={T} N={N} K={K}")
@@ -402,18 +405,20 @@ def test_gemm_parity(B, orc, T, N, K):
 
 
 @pytest.mark.parametrize("K,N", [(320, 260), (328, 260), (328, 262)])   # ..., zero-filled last panel, generic kernel
+@pytest.mark.parametrize("T", [300, 70000])   # one tile per workgroup / two tiles on some (persistent loop)
 @pytest.mark.parametrize("odt", [np.float32, np.float16])
-def test_gemm_dequant_epilogue(B, orc, odt, K, N):
-    progress(f"gemm dequant epilogue {odt.__name__} K={K} N={N}")
+def test_gemm_dequant_epilogue(B, orc, odt, K, N, T):
+    progress(f"gemm dequant epilogue {odt.__name__} K={K} N={N} T={T}")
     rng = np.random.default_rng(3)
-    T = 300
     xq = rng.integers(-128, 128, (T, K), dtype=np.int8)
     wq = rng.integers(-128, 128, (N, K), dtype=np.int8)
     deq = dict(dtype=odt, step_x=0.0123, zero_x=141, step_w=rng.uniform(1e-4, 1e-3, N).astype(np.float32),
                zero_w=rng.integers(90, 170, N).astype(np.int32), bias=rng.standard_normal(N).astype(np.float32),
                rowsum_x=xq.astype(np.int64).sum(axis=1).astype(np.int32), rowsum_w=wq.astype(np.int64).sum(axis=1).astype(np.int32))
-    _, out_deq, cs = gpu_gemm(B, xq, wq, deq=deq)
-    assert np.array_equal(host(cs), orc.gemm_i8(xq, wq).astype(np.int64).sum(axis=0))
+    out, out_deq, cs = gpu_gemm(B, xq, wq, deq=deq)
+    acc = orc.gemm_i8(xq, wq)
+    assert np.array_equal(host(out), acc)            # the raw accumulator written next to the de-quantised output
+    assert np.array_equal(host(cs), acc.astype(np.int64).sum(axis=0))
     ref = orc.w8a8_output_direct(xq, wq, deq["step_x"], deq["zero_x"], deq["step_w"], deq["zero_w"], deq["bias"])
     got = host(out_deq).astype(np.float64)
     if odt == np.float32:
