@@ -43,12 +43,110 @@ def parse():
     ap.add_argument("--weight-only", type=int, default=0, choices=(0, 3, 4),
                     help="weight-only calibration (BASELINE.json configs[3]): W4 or W3 per group of 128, fp16 activations "
                          "(statistics, equalization, weight quantizer, bias correction; no GEMM); implies --cfg 4")
+    ap.add_argument("--block", action="store_true",
+                    help="run the block with its real data flow: linears that read the same activation (q/k/v, gate/up) "
+                         "share one statistics pass, one equalization scale and one activation quantization")
     ap.add_argument("--layers", default="", help="comma-separated layer names to keep (profiling runs)")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="only measure the sustained shader clock / MFMA rate for three kinds of operand data and exit")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="only run a plain device copy of this many bytes (reference for the HBM counters) and exit")
     return ap.parse_args()
+
+
+SHARED_INPUT_GROUPS = (("q_proj", "k_proj", "v_proj"), ("gate_proj", "up_proj"))
+
+
+def block_bench(args, torch, B, pipeline, synth, dev):
+    """W8A8 calibration of a block with shared inputs (Sec. 3.1: equalization sits at the entrance of
+    the attention block and of the MLP): the call sequence of pipeline.calibrate_group with the GEMMs
+    bracketed by events."""
+    wl = synth.WORKLOADS[args.cfg]
+    T = args.tokens or wl.T
+    tdt = torch.float16 if wl.dtype == "f16" else torch.float32
+    dt = B.AWEQ_F16 if wl.dtype == "f16" else B.AWEQ_F32
+    groups, seen = [], set()
+    for li, lin in enumerate(wl.linears):
+        if lin.name in seen:
+            continue
+        names = next((g for g in SHARED_INPUT_GROUPS if lin.name in g), (lin.name,))
+        members = [(j, l) for j, l in enumerate(wl.linears) if l.name in names]
+        seen.update(l.name for _, l in members)
+        seed = synth.layer_seed(wl.cfg, li)
+        X = synth.make_act_torch(seed, T, lin.K, wl, dev)
+        Ws = [synth.make_weight_torch(synth.layer_seed(wl.cfg, j), l.N, l.K, wl.dtype, dev) for j, l in members]
+        bs = []
+        for j, l in members:
+            b = synth.make_bias_np(synth.layer_seed(wl.cfg, j), l.N, wl.has_bias)
+            bs.append(torch.from_numpy(b).to(dev) if b is not None else None)
+        gb = pipeline.GroupBuffers(T, lin.K, tuple(l.N for _, l in members), tdt, want_out_i32=True, device=dev)
+        groups.append(([l for _, l in members], X, Ws, bs, gb))
+    torch.cuda.synchronize()
+    n_layers = sum(len(g[0]) for g in groups)
+
+    def run_group(lins, X, Ws, bs, gb, ev=None):
+        t, K, st = gb.t, gb.K, gb.t["status"]
+        B.aweq_calib_stats(X, dt, T, K, K, t["xmin"], t["xmax"], t["xsum"], t["count"], 0, 1, t["r_x"], t["R_x"],
+                           t["p_x"], t["ws"], st)
+        for i, W in enumerate(Ws):
+            B.aweq_calib_stats(W, dt, W.shape[0], K, K, t["wmin"], t["wmax"], None, t["wcount"], int(i > 0),
+                               int(i == len(Ws) - 1), t["r_w"], t["R_w"], t["p_w"], t["ws"], st)
+        for W, p in zip(Ws, gb.per):
+            N = W.shape[0]
+            B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, 1, t["s"], t["inv_s"], W,
+                            p["W_hat"], dt, N, K, None, t["xhat_range"], t["mu_xhat"], t["act_step"], t["act_zero"], st)
+            B.aweq_quant_weight(p["W_hat"], dt, N, K, K, 8, 0, p["codes"], p["step_w"], p["zero_w"], p["rowsum_w"],
+                                t["ws"], st)
+        B.aweq_quant_act(X, dt, T, K, K, t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],
+                         t["colsum_xq"], st)
+        for i, (W, b, p) in enumerate(zip(Ws, bs, gb.per)):
+            N = W.shape[0]
+            if ev is not None:
+                ev[i][0].record()
+            B.aweq_w8a8_gemm(t["xq"], B.AWEQ_I8, T, K, K, None, t["act_step"], t["act_zero"], None, t["rowsum_x"], None,
+                             p["codes"], N, p["step_w"], p["zero_w"], p["rowsum_w"], b, p["out_i32"], None, dt, N,
+                             p["colsum_acc"], None, st)
+            if ev is not None:
+                ev[i][1].record()
+            B.aweq_bias_correct(B.BIAS_W8A8, p["W_hat"], dt, N, K, K, t["mu_xhat"], T, p["colsum_acc"], t["colsum_xq"],
+                                p["rowsum_w"], t["act_step"], t["act_zero"], None, 8, 0, p["step_w"], p["zero_w"], b,
+                                p["delta"], p["bias_out"], 1, None, st)
+
+    for _ in range(args.warmup):
+        for g in groups:
+            run_group(*g)
+    torch.cuda.synchronize()
+    evs = [[[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in g[0]] for g in groups]
+           for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        for gi, g in enumerate(groups):
+            run_group(*g, evs[k][gi])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    gemm_ms = sum(e0.elapsed_time(e1) for k in range(args.steps) for gi in range(len(groups)) for e0, e1 in evs[k][gi])
+    gemm_ops = args.steps * sum(2.0 * T * l.N * l.K for g in groups for l in g[0])
+    gemm_tops = gemm_ops / (gemm_ms * 1e-3) / 1e12
+    status_bits = 0
+    for g in groups:
+        status_bits |= int(g[4].t["status"].item())
+    return {
+        "metric": "calibration tokens/sec per layer (stats+equalize+quant+bias); W8A8 GEMM TOPS",
+        "value": n_layers * T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"cfg{wl.cfg} {wl.name}: {n_layers} linears on {len(groups)} distinct inputs (shared-input "
+                               f"groups {[[l.name for l in g[0]] for g in groups]}), T={T} calibration tokens, {wl.dtype} in, "
+                               "W8 per-channel / A8 per-tensor, GEMM output int32 + column sums",
+                   "value_is": "layers * T / step time, whole block with one statistics pass and one activation "
+                               "quantization per distinct input"},
+        "gemm_tops": gemm_tops,
+        "roofline": {"bound": "mfma", "kernel": "gemm_i8_fast", "achieved": gemm_tops, "peak": INT8_PEAK_TOPS,
+                     "unit": "TFLOP/s", "frac": gemm_tops / INT8_PEAK_TOPS, "traffic": None,
+                     "note": "int8 multiply-add = 2 ops (TOP/s); achieved = sum 2*T*N*K / sum of event-timed GEMM launches"},
+        "status_bits": status_bits,
+    }
 
 
 def weight_only_bench(args, torch, B, pipeline, synth, dev):
@@ -227,6 +325,9 @@ def main():
         return
     if args.weight_only:
         print(json.dumps(weight_only_bench(args, torch, B, pipeline, synth, dev)))
+        return
+    if args.block:
+        print(json.dumps(block_bench(args, torch, B, pipeline, synth, dev)))
         return
     wl = synth.WORKLOADS[args.cfg]
     T = args.tokens or wl.T
