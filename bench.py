@@ -368,11 +368,12 @@ def main():
         B.aweq_calib_stats(W, dt, N, K, K, t["wmin"], t["wmax"], None, t["wcount"], 0, 1, t["r_w"], t["R_w"],
                            t["p_w"], t["ws"], st)
         mark(2)
-        B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, 1, t["s"], t["inv_s"], W,
-                        t["W_hat"], dt, N, K, None, t["xhat_range"], t["mu_xhat"], t["act_step"], t["act_zero"], st)
+        B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, 1, t["s"], t["inv_s"], None,
+                        None, dt, N, K, None, t["xhat_range"], t["mu_xhat"], t["act_step"], t["act_zero"], st)
         mark(3)
-        B.aweq_quant_weight(t["W_hat"], dt, N, K, K, 8, 0, t["codes"], t["step_w"], t["zero_w"], t["rowsum_w"],
-                            t["ws"], st)
+        # fold (Eq. 3) and per-channel quantizer in one pass over W
+        B.aweq_fold_quant_weight(W, dt, N, K, K, t["s"], t["W_hat"], 8, t["codes"], t["step_w"], t["zero_w"],
+                                 t["rowsum_w"], st)
         mark(4)
         B.aweq_quant_act(X, dt, T, K, K, t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],
                          t["colsum_xq"], st)

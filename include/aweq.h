@@ -135,6 +135,14 @@ int aweq_quant_weight(const void* W_hat, aweq_dtype dt, int64_t N, int64_t K, in
                       int32_t* rowsum_w, void* ws, size_t ws_bytes,
                       uint32_t* status, void* stream);
 
+/* ---- Stages 2b + 3 in one pass over W (per-row quantizer, group = 0): W_hat[n,k] = W[n,k] * s[k]
+ * rounded to dt (Eq. 3; W_hat has W's pitch and may alias W) is written and quantised from registers,
+ * with the outputs of aweq_quant_weight(group = 0).  Same results as aweq_equalize's fold followed by
+ * aweq_quant_weight; call aweq_equalize with W = NULL for the scales first. */
+int aweq_fold_quant_weight(const void* W, aweq_dtype dt, int64_t N, int64_t K, int64_t ldw,
+                           const float* s, void* W_hat, int bits, void* codes, float* step,
+                           int32_t* zero, int32_t* rowsum_w, uint32_t* status, void* stream);
+
 /* ---- Stage 4a (helper, also run by aweq_w8a8_gemm): static per-tensor int8 activation
  * quantizer (Eq. 1 with b = 8) applied to X_hat = X * inv_s on the fly:
  * xq[t,k] = clamp(round((X[t,k] * inv_s[k]) / Step_x) + Z_x, 0, 255) - 128,

@@ -19,7 +19,7 @@ ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD = 1, 2, 4, 8
 
 EXPORTS = ("aweq_workspace_size", "aweq_status_string", "aweq_calib_stats", "aweq_equalize",
            "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock",
-           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8", "aweq_wonly_gemm")
+           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8", "aweq_wonly_gemm", "aweq_fold_quant_weight")
 
 _vp, _i64, _i32, _u64, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_float, C.c_size_t
 
@@ -68,6 +68,8 @@ def load_library():
     lib.aweq_wonly_gemm.restype = _i32
     lib.aweq_wonly_gemm.argtypes = [_vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _i64, _vp, _vp, _i32, _i64, _vp, _sz,
                                     _vp, _vp]
+    lib.aweq_fold_quant_weight.restype = _i32
+    lib.aweq_fold_quant_weight.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]
     lib.aweq_panel_bytes.restype = _sz
     lib.aweq_panel_bytes.argtypes = [_i64, _i64]
     lib.aweq_pack_panels_i8.restype = _i32
@@ -183,3 +185,8 @@ def aweq_wonly_gemm(X_hat, T, K, ldx, codes, bits, group, step_w, zero_w, N, bia
                                           _ptr(zero_w), N, _ptr(bias), _ptr(out), out_dt, ldo, _ptr(ws),
                                           _nbytes(ws) if ws_bytes is None else ws_bytes, _ptr(status),
                                           _stream(stream)))
+
+
+def aweq_fold_quant_weight(W, dt, N, K, ldw, s, W_hat, bits, codes, step, zero, rowsum_w, status=None, stream=None):
+    _check(load_library().aweq_fold_quant_weight(_ptr(W), dt, N, K, ldw, _ptr(s), _ptr(W_hat), int(bits), _ptr(codes),
+                                                 _ptr(step), _ptr(zero), _ptr(rowsum_w), _ptr(status), _stream(stream)))

@@ -31,6 +31,16 @@ struct Unit<true> {
             x[2 * i + 1] = f.y;
         }
     }
+    // round to binary16 and keep
+    __device__ __forceinline__ void set(const float x[8])
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) raw.h[i] = f16x2{(_Float16)x[2 * i], (_Float16)x[2 * i + 1]};
+    }
+    __device__ __forceinline__ void store(void* row, int64_t u) const
+    {
+        *reinterpret_cast<Half8*>(reinterpret_cast<_Float16*>(row) + u * 8) = raw;
+    }
 };
 
 template <>
@@ -46,6 +56,17 @@ struct Unit<false> {
     {
 #pragma unroll
         for (int i = 0; i < 4; ++i) { x[i] = raw[0].f[i]; x[4 + i] = raw[1].f[i]; }
+    }
+    __device__ __forceinline__ void set(const float x[8])
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { raw[0].f[i] = x[i]; raw[1].f[i] = x[4 + i]; }
+    }
+    __device__ __forceinline__ void store(void* row, int64_t u) const
+    {
+        float* p = reinterpret_cast<float*>(row) + u * 8;
+        *reinterpret_cast<Float4*>(p) = raw[0];
+        *reinterpret_cast<Float4*>(p + 4) = raw[1];
     }
 };
 
@@ -103,10 +124,13 @@ __device__ __forceinline__ int quant_store_unit(const float x[8], float step, in
 
 // ---- one (Step, Z) per row, or one for the tensor (PER_TENSOR: read from step[0]/zero[0]).
 // 8-bit codes are the GEMM's weight operand and go out in its K-panel layout.
-template <bool F16, int BITS, bool PER_TENSOR>
+// FOLD: the row read is the un-equalised W; it is multiplied by s[k] (one fp32 multiply, rounded to
+// the weight's type: Eq. 3), written to W_hat and quantised from registers, so W is read once.
+template <bool F16, int BITS, bool PER_TENSOR, bool FOLD = false>
 __global__ __launch_bounds__(kQwBlock) void quant_weight_row(
     const void* __restrict__ W, int64_t K, int64_t ldw, uint8_t* __restrict__ codes,
-    float* __restrict__ step, int32_t* __restrict__ zero, int32_t* __restrict__ rowsum_w, uint32_t* status)
+    float* __restrict__ step, int32_t* __restrict__ zero, int32_t* __restrict__ rowsum_w, uint32_t* status,
+    const float* __restrict__ s = nullptr, void* __restrict__ W_hat = nullptr, int64_t ldwh = 0)
 {
     __shared__ float slot_f[kQwBlock / kWave];
     __shared__ int slot_i[kQwBlock / kWave];
@@ -124,6 +148,15 @@ __global__ __launch_bounds__(kQwBlock) void quant_weight_row(
         const int64_t u = threadIdx.x + (int64_t)j * kQwBlock;
         if (u < units) {
             reg[j].load(row, u);
+            if constexpr (FOLD) {
+                float x[8];
+                reg[j].get(x);
+                const Float4 s0 = *reinterpret_cast<const Float4*>(s + u * 8), s1 = *reinterpret_cast<const Float4*>(s + u * 8 + 4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { x[i] = x[i] * s0.f[i]; x[4 + i] = x[4 + i] * s1.f[i]; }
+                reg[j].set(x);
+                reg[j].store(reinterpret_cast<char*>(W_hat) + (size_t)n * ldwh * (F16 ? 2 : 4), u);
+            }
             if constexpr (!PER_TENSOR) {
                 float x[8];
                 reg[j].get(x);
@@ -322,5 +355,29 @@ extern "C" int aweq_quant_weight(const void* W_hat, aweq_dtype dt, int64_t N, in
         if (bits == 8) { AWEQ_DISPATCH(false, 8) } else if (bits == 4) { AWEQ_DISPATCH(false, 4) } else { AWEQ_DISPATCH(false, 3) }
     }
 #undef AWEQ_DISPATCH
+    return launch_status();
+}
+
+// Fold and quantise in one pass over W (per-row quantizer): what aweq_equalize's fold followed by
+// aweq_quant_weight with group = 0 produce, with W read once and W_hat not read back.
+extern "C" int aweq_fold_quant_weight(const void* W, aweq_dtype dt, int64_t N, int64_t K, int64_t ldw,
+                                      const float* s, void* W_hat, int bits, void* codes, float* step,
+                                      int32_t* zero, int32_t* rowsum_w, uint32_t* status, void* stream)
+{
+    if (!W || !s || !W_hat || !codes || !step || !zero) return AWEQ_ERR_NULL;
+    if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
+    if (bits != 8 && bits != 4 && bits != 3) return AWEQ_ERR_BITS;
+    if (N <= 0 || N > 0x7fffffffll || K <= 0 || ldw < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
+    if (K > (int64_t)kQwBlock * 8 * kQwMaxUnits) return AWEQ_ERR_SHAPE;  // a row must fit the block's registers
+    if (bits == 3 && (K % 32) != 0) return AWEQ_ERR_ALIGN;
+    if (bits != 8 && rowsum_w) return AWEQ_ERR_BITS;
+    if (!aligned16(W) || !aligned16(W_hat) || !aligned16(s) || ((size_t)ldw * dtype_size(dt)) % 16 != 0 || !aligned16(codes))
+        return AWEQ_ERR_ALIGN;
+    hipStream_t st = as_stream(stream);
+    uint8_t* cb = reinterpret_cast<uint8_t*>(codes);
+#define AWEQ_FQ(F, B) quant_weight_row<F, B, false, true><<<(unsigned)N, kQwBlock, 0, st>>>(W, K, ldw, cb, step, zero, rowsum_w, status, s, W_hat, ldw)
+    if (dt == AWEQ_F16) { if (bits == 8) AWEQ_FQ(true, 8); else if (bits == 4) AWEQ_FQ(true, 4); else AWEQ_FQ(true, 3); }
+    else { if (bits == 8) AWEQ_FQ(false, 8); else if (bits == 4) AWEQ_FQ(false, 4); else AWEQ_FQ(false, 3); }
+#undef AWEQ_FQ
     return launch_status();
 }

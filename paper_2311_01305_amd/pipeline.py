@@ -72,7 +72,7 @@ class LayerBuffers:
 
 
 def calibrate_layer(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], buf: LayerBuffers,
-                    enable_awe: bool = True, enable_bc: bool = True, stream=None):
+                    enable_awe: bool = True, enable_bc: bool = True, stream=None, fused_weight_pass: bool = False):
     """One pass of the whole hot path for one linear layer.  Everything is enqueued on the
     current (or given) stream; nothing synchronises."""
     t = buf.t
@@ -84,13 +84,18 @@ def calibrate_layer(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tenso
                        t["r_x"], t["R_x"], t["p_x"], t["ws"], st, stream)
     B.aweq_calib_stats(W, dt, N, K, W.stride(0), t["wmin"], t["wmax"], None, t["wcount"], 0, 1,
                        t["r_w"], t["R_w"], t["p_w"], t["ws"], st, stream)
+    fused = fused_weight_pass and buf.group == 0 and W.stride(0) == K
     # stage 2: equalization scales, fold into W, equalised activation range / mean / quantizer
     B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, enable_awe, t["s"], t["inv_s"],
-                    W, t["W_hat"], dt, N, W.stride(0), None, t["xhat_range"], t["mu_xhat"], t["act_step"],
-                    t["act_zero"], st, stream)
-    # stage 3: weight quantizer
-    B.aweq_quant_weight(t["W_hat"], dt, N, K, K, buf.bits, buf.group, t["codes"], t["step_w"], t["zero_w"],
-                        t["rowsum_w"] if (buf.bits == 8 and buf.group <= 0) else None, t["ws"], st, stream)
+                    None if fused else W, t["W_hat"], dt, N, W.stride(0), None, t["xhat_range"], t["mu_xhat"],
+                    t["act_step"], t["act_zero"], st, stream)
+    # stage 3: weight quantizer (fused: fold and quantise in one pass over W)
+    if fused:
+        B.aweq_fold_quant_weight(W, dt, N, K, K, t["s"], t["W_hat"], buf.bits, t["codes"], t["step_w"], t["zero_w"],
+                                 t["rowsum_w"] if buf.bits == 8 else None, st, stream)
+    else:
+        B.aweq_quant_weight(t["W_hat"], dt, N, K, K, buf.bits, buf.group, t["codes"], t["step_w"], t["zero_w"],
+                            t["rowsum_w"] if (buf.bits == 8 and buf.group <= 0) else None, t["ws"], st, stream)
     if buf.w8a8:
         # stage 4: activation quantizer + int8 GEMM (+ per-channel output sums for stage 5)
         B.aweq_w8a8_gemm(X, dt, T, K, X.stride(0), t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],

@@ -38,7 +38,7 @@ def run():
     b = torch.from_numpy(synth.make_bias_np(seed, lin.N, wl.has_bias)).to(DEV)
     buf = pipeline.LayerBuffers(wl.T, lin.K, lin.N, torch.float16, want_out_i32=True, want_out_deq=False, device=DEV)
     progress("running the whole path")
-    t = pipeline.calibrate_layer(X, W, b, buf)
+    t = pipeline.calibrate_layer(X, W, b, buf, fused_weight_pass=True)  # the call sequence bench.py times
     torch.cuda.synchronize()
     return dict(wl=wl, lin=lin, X=X, W=W, b=b, t=t)
 

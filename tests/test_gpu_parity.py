@@ -257,6 +257,37 @@ def test_quant_weight_degenerate_and_half_ties(B, orc):
     assert np.all(from_panels(host(g["codes"]), 3, 128).view(np.int8) == -128) and int(host(g["status"])[0]) & B.ST_DEGENERATE
 
 
+@pytest.mark.parametrize("dtype,N,K,bits", [(np.float16, 37, 4096, 8), (np.float16, 5, 11008, 8), (np.float32, 64, 520, 8),
+                                             (np.float16, 11, 2048, 4), (np.float16, 11, 2048, 3)])
+def test_fold_quant_weight_equals_two_calls(B, orc, dtype, N, K, bits):
+    """The fused fold + per-row quantizer against the oracle's fold followed by its quantizer."""
+    progress(f"fold+quant {dtype.__name__} N={N} K={K} b={bits}")
+    rng = np.random.default_rng(N + K + bits)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(dtype)
+    s = rng.uniform(0.2, 5.0, K).astype(np.float32)
+    Wh = orc.fold_weight(W, s)
+    o = orc.quant_weight(Wh, bits, 0)
+    panel = bits == 8
+    codes = torch.full((B.aweq_panel_bytes(N, K) if panel else N * K * bits // 8,), 0x5a, dtype=torch.uint8, device=DEV)
+    step, zero = e(N, dtype=torch.float32), e(N, dtype=torch.int32)
+    rowsum = e(N, dtype=torch.int32) if bits == 8 else None
+    W_hat = torch.zeros((N, K), dtype=torch.float16 if dtype == np.float16 else torch.float32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    B.aweq_fold_quant_weight(dev(W), dtc(B, W), N, K, K, dev(s), W_hat, bits, codes, step, zero, rowsum, status)
+    assert np.array_equal(host(W_hat).view(np.uint8), Wh.view(np.uint8))
+    assert np.array_equal(host(step), o["step"]) and np.array_equal(host(zero), o["zero"])
+    got = host(codes)
+    if panel:
+        got = from_panels(got, N, K).reshape(-1)
+        assert np.array_equal(host(rowsum), o["rowsum_w"])
+    assert np.array_equal(got, orc.pack_codes(o["codes_u"], bits).view(np.uint8).reshape(-1))
+    assert int(host(status)[0]) == o["status"]
+    # in place: W_hat aliasing W
+    Wd = dev(W)
+    B.aweq_fold_quant_weight(Wd, dtc(B, W), N, K, K, dev(s), Wd, bits, codes, step, zero, rowsum, status)
+    assert np.array_equal(host(Wd).view(np.uint8), Wh.view(np.uint8)) and np.array_equal(host(zero), o["zero"])
+
+
 # ------------------------------------------------------------------------------ stage 4a
 
 

@@ -204,3 +204,14 @@ def test_wonly_gemm_argument_errors(B):
     assert _code(call, ldo=32) == "AWEQ_ERR_SHAPE"
     assert _code(call, out_dt=B.AWEQ_I8) == "AWEQ_ERR_DTYPE"
     assert _code(call, X_hat=P + 2) == "AWEQ_ERR_ALIGN"
+
+
+def test_fold_quant_weight_argument_errors(B):
+    P = 0x10000
+    ok = dict(W=P, dt=B.AWEQ_F16, N=8, K=64, ldw=64, s=P, W_hat=P, bits=8, codes=P, step=P, zero=P, rowsum_w=P, stream=0)
+    call = lambda **kw: B.aweq_fold_quant_weight(**{**ok, **kw})
+    assert _code(call, s=None) == "AWEQ_ERR_NULL"
+    assert _code(call, bits=5) == "AWEQ_ERR_BITS"
+    assert _code(call, bits=4) == "AWEQ_ERR_BITS"            # row sums are an int8 notion
+    assert _code(call, K=24584, ldw=24584) == "AWEQ_ERR_SHAPE"
+    assert _code(call, W=P + 8) == "AWEQ_ERR_ALIGN"
