@@ -435,6 +435,22 @@ def test_gemm_parity(B, orc, T, N, K):
     assert np.array_equal(host(cs2), host(cs))
 
 
+def test_gemm_largest_contraction_and_extreme_accumulators(B, orc):
+    """K = 32768 is the largest contraction the int32 accumulator is guaranteed for: all-(-128) rows
+    give 128 * 128 * 32768 = 2^29, mixed signs give -(127 * 128 * 32768); column sums stay exact."""
+    progress("gemm K=32768, extreme accumulators")
+    rng = np.random.default_rng(8)
+    T, N, K = 260, 256, 32768
+    xq = rng.integers(-128, 128, (T, K), dtype=np.int8)
+    wq = rng.integers(-128, 128, (N, K), dtype=np.int8)
+    xq[0], xq[1], wq[0], wq[1] = -128, 127, -128, 127
+    out, _, cs = gpu_gemm(B, xq, wq)
+    ref = orc.gemm_i8(xq, wq)
+    assert ref[0, 0] == 2 ** 29 and ref[1, 0] == -127 * 128 * 32768 and ref[1, 1] == 127 * 127 * 32768
+    assert np.array_equal(host(out), ref)
+    assert np.array_equal(host(cs), ref.astype(np.int64).sum(axis=0))
+
+
 @pytest.mark.parametrize("K,N", [(320, 260), (328, 260), (328, 262)])   # ..., zero-filled last panel, generic kernel
 @pytest.mark.parametrize("T", [300, 70000])   # one tile per workgroup / two tiles on some (persistent loop)
 @pytest.mark.parametrize("odt", [np.float32, np.float16])
