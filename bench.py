@@ -278,12 +278,13 @@ def mfma_probe(torch, B, dev, iters=20000, reps=12):
     out = torch.zeros(3, dtype=torch.int64, device=dev)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     res = {}
-    for mode, name in ((0, "constant_bytes"), (1, "random_bytes"), (2, "small_signed_codes")):
+    for mode, name, ops in ((0, "constant_bytes", 65536), (1, "random_bytes", 65536), (2, "small_signed_codes", 65536),
+                            (3, "f16_32x32x16_random_values", 32768)):
         for _ in range(reps):  # the clock settles over a few tens of milliseconds
             B.aweq_probe_mfma_clock(iters, mode, out)
         cyc, ticks = int(out[0].item()), int(out[1].item())
         res[name] = {"shader_clock_GHz": cyc / ticks * 0.1, "cycles_per_mfma": cyc / (16.0 * iters),
-                     "TOPs": cus * 4 * 16.0 * iters * 65536 / (ticks * 1e-8) / 1e12}
+                     "TOPs": cus * 4 * 16.0 * iters * ops / (ticks * 1e-8) / 1e12}
     return {"mfma_probe": res, "compute_units": cus}
 
 

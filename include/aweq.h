@@ -212,7 +212,8 @@ int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t ldx,
 /* ---- Diagnostic (not a stage of the method; for measurement reports).  One workgroup of four
  * wavefronts per compute unit issues iters x 16 back-to-back independent int8 32x32x32 MFMAs with
  * operand registers holding constant bytes (operand_mode 0), uniformly random bytes (1) or small
- * signed codes (2), and no memory traffic.  out[3] (device, uint64): shader-clock cycles of one
+ * signed codes (2), and no memory traffic; operand_mode 3: the same loop with the binary16
+ * 32x32x16 MFMA (32768 flop each) on activation- and weight-like binary16 values.  out[3] (device, uint64): shader-clock cycles of one
  * wavefront's loop, 100 MHz reference ticks of the same interval, a checksum.  The sustained
  * shader clock under matrix load is out[0] / out[1] x 100 MHz; the MFMA rate is
  * CUs x 4 x 16 x iters x 65536 ops over out[1] x 10 ns. */

@@ -9,6 +9,47 @@ namespace aweq {
 
 typedef int pv4i __attribute__((ext_vector_type(4)));
 typedef int pv16i __attribute__((ext_vector_type(16)));
+typedef _Float16 pv8h __attribute__((ext_vector_type(8)));
+typedef float pv16f __attribute__((ext_vector_type(16)));
+
+// operand_mode 3: the same loop with v_mfma_f32_32x32x16_f16 on binary16 operands that look like
+// activations (unit scale) and de-quantised weights (scale 0.02)
+__global__ __launch_bounds__(256) void mfma_clock_probe_f16(int iters, unsigned long long* out)
+{
+    pv8h a[4], b[4];
+    unsigned x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    for (int i = 0; i < 4; ++i)
+        for (int c = 0; c < 8; ++c) {
+            x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+            const float ua = (float)(int)(x & 0xffff) * (1.0f / 32768.0f) - 1.0f;
+            x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+            const float ub = (float)(int)(x & 0xffff) * (1.0f / 32768.0f) - 1.0f;
+            a[i][c] = (_Float16)(2.0f * ua);
+            b[i][c] = (_Float16)(0.04f * ub);
+        }
+    pv16f acc[4][4];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    const unsigned long long c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    float s = 0.0f;
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int v = 0; v < 16; ++v) s += acc[i][j][v];
+    const unsigned long long c1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        out[0] = c1 - c0;
+        out[1] = r1 - r0;
+        out[2] = (unsigned long long)__float_as_uint(s);  // keeps the accumulators alive
+    }
+}
 
 __global__ __launch_bounds__(256) void mfma_clock_probe(int iters, int operand_mode, unsigned long long* out)
 {
@@ -65,11 +106,14 @@ __global__ __launch_bounds__(256) void mfma_clock_probe(int iters, int operand_m
 extern "C" int aweq_probe_mfma_clock(int iters, int operand_mode, uint64_t* out, void* stream)
 {
     if (!out) return AWEQ_ERR_NULL;
-    if (iters <= 0 || iters > (1 << 22) || operand_mode < 0 || operand_mode > 2) return AWEQ_ERR_SHAPE;
+    if (iters <= 0 || iters > (1 << 22) || operand_mode < 0 || operand_mode > 3) return AWEQ_ERR_SHAPE;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return AWEQ_ERR_LAUNCH;
-    aweq::mfma_clock_probe<<<(unsigned)cus, 256, 0, aweq::as_stream(stream)>>>(iters, operand_mode,
-                                                                               reinterpret_cast<unsigned long long*>(out));
+    if (operand_mode == 3)
+        aweq::mfma_clock_probe_f16<<<(unsigned)cus, 256, 0, aweq::as_stream(stream)>>>(iters, reinterpret_cast<unsigned long long*>(out));
+    else
+        aweq::mfma_clock_probe<<<(unsigned)cus, 256, 0, aweq::as_stream(stream)>>>(iters, operand_mode,
+                                                                                   reinterpret_cast<unsigned long long*>(out));
     return aweq::launch_status();
 }
