@@ -163,7 +163,9 @@ int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t l
  * out_deq[T x N] (F16 or F32, pitch ldo) the de-quantised output
  *   Step_x Step_w[n] (acc - Z'x rowsum_w[n] - Z'w[n] rowsum_x[t] + K Z'x Z'w[n]) + bias[n],
  *   Z' = Z - 128 (needs rowsum_x, rowsum_w, step_w, zero_w; bias nullable);
- * colsum_acc[N] = sum_t acc[t,n] (int64; what stage 5 needs). */
+ * colsum_acc[N] = sum_t acc[t,n] (int64; what stage 5 needs).
+ * step_w / zero_w / rowsum_w are indexed by output channel here and in aweq_bias_correct (W8A8
+ * mode): for a per-tensor weight quantizer (group = -1) pass the one (Step, Z) repeated N times. */
 int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t K, int64_t ldx,
                    const float* inv_s, const float* act_step, const int32_t* act_zero,
                    int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,

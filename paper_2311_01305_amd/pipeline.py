@@ -51,6 +51,8 @@ class LayerBuffers:
         t["status"] = torch.zeros(1, dtype=i32, device=d)
         t["W_hat"] = e(N, K, dtype=self.dtype)
         ng = 1 if self.group < 0 else (N if self.group == 0 else N * (K // self.group))
+        if self.group < 0 and self.w8a8:
+            ng = N  # the GEMM epilogue and the bias correction index (Step, Z) by output channel
         # 8-bit per-row / per-tensor codes are the GEMM operand: K-panel layout
         panel_w = self.bits == 8 and self.group <= 0
         t["codes"] = e(B.aweq_panel_bytes(N, K) if panel_w else N * K * self.bits // 8, dtype=torch.int8)
@@ -96,6 +98,10 @@ def calibrate_layer(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tenso
     else:
         B.aweq_quant_weight(t["W_hat"], dt, N, K, K, buf.bits, buf.group, t["codes"], t["step_w"], t["zero_w"],
                             t["rowsum_w"] if (buf.bits == 8 and buf.group <= 0) else None, t["ws"], st, stream)
+    if buf.w8a8 and buf.group < 0:
+        # per-tensor weights (Sec. 3): the one (Step, Z) is repeated for every output channel (a copy)
+        t["step_w"][1:].copy_(t["step_w"][0].expand(N - 1))
+        t["zero_w"][1:].copy_(t["zero_w"][0].expand(N - 1))
     if buf.w8a8:
         # stage 4: activation quantizer + int8 GEMM (+ per-channel output sums for stage 5)
         B.aweq_w8a8_gemm(X, dt, T, K, X.stride(0), t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],

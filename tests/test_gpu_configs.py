@@ -131,6 +131,36 @@ def test_weight_only_layer_shapes(mods, orc, li, bits):
     assert int(h(t["status"])[0]) == 0
 
 
+def test_w8a8_per_tensor_weights(mods, orc):
+    """The paper's own stated granularity (Sec. 3: per-tensor for weights and activations) through the
+    whole W8A8 path: one (Step, Z) for the weight, repeated per output channel for stages 4 and 5."""
+    B, pipeline, synth = mods
+    wl = synth.scaled(synth.WORKLOADS[3], 768, [synth.Linear("fc", 320, 512)])
+    progress("W8A8 with per-tensor weight quantizer")
+    seed, T, K, N = 777, 768, 512, 320
+    W = synth.make_weight_np(seed, N, K, wl.dtype)
+    X = synth.make_act_np(seed, T, K, wl)
+    buf = pipeline.LayerBuffers(T, K, N, torch.float16, group=-1, want_out_i32=True, want_out_deq=True, device=DEV)
+    t = pipeline.calibrate_layer(dev(X), dev(W), None, buf)
+    Wh, gi, lo, hi = front(orc, X, W, t)
+    step, zero, _ = orc.qparams(lo, hi, 8)
+    q = orc.quant_weight(Wh, 8, -1)
+    assert q["step"].size == 1
+    sw, zw = np.full(N, q["step"].reshape(-1)[0], np.float32), np.full(N, q["zero"].reshape(-1)[0], np.int32)
+    assert np.array_equal(h(t["step_w"]), sw) and np.array_equal(h(t["zero_w"]), zw)
+    wq = orc.pack_codes(q["codes_u"], 8)
+    assert np.array_equal(from_panels(h(t["codes"]), N, K), wq)
+    a = orc.quant_act(X, gi, step, zero)
+    acc = orc.gemm_i8(a["xq"], wq)
+    assert np.array_equal(h(t["out_i32"]), acc)
+    csa = acc.astype(np.int64).sum(axis=0)
+    d_ref, _ = orc.bias_w8a8(Wh, h(t["mu_xhat"]), T, csa, a["colsum_xq"], q["rowsum_w"], step, zero, sw, zw, None)
+    assert np.max(np.abs(h(t["delta"]) - d_ref)) <= 1e-5 * np.max(np.abs(d_ref))
+    ref = orc.w8a8_output_direct(a["xq"], wq, step, zero, sw, zw, None)
+    got = h(t["out_deq"]).astype(np.float64)
+    assert np.all(np.abs(got - ref) <= np.maximum(np.abs(ref), 2.0 ** -14) * 2.0 ** -10)
+
+
 def test_ablation_switches(mods, orc):
     """AWE x BC grid of Sec. 4.4 on one small layer: every combination runs; AWE off gives
     s = 1, BC off leaves the bias alone; with outlier channels AWE lowers the W8A8 output error."""
