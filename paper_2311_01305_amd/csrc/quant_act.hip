@@ -121,7 +121,8 @@ template <> struct RawUnit<false> {
     }
 };
 
-// grid (column chunks of 8 panels, row slices).  The codes go out in the K-panel layout the
+// One-dimensional grid, workgroup id = slice * chunks + chunk (column chunks of 8 panels vary fastest:
+// neighbouring workgroups then read neighbouring kilobytes of the same rows).  The codes go out in the K-panel layout the
 // GEMM reads (64-byte panels, rows back to back), so a wavefront works on 8 rows x one panel
 // per instruction: lane = 8 (row % 8) + unit; its load covers 8 whole 128-byte lines of
 // binary16 input and its store 512 contiguous bytes of codes.  Each wavefront owns two
@@ -130,19 +131,22 @@ template <bool F16>
 __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     const void* __restrict__ X, int64_t T, int64_t K, int64_t ldx, const float* __restrict__ inv_s,
     const float* __restrict__ act_step, const int32_t* __restrict__ act_zero, int8_t* __restrict__ xq,
-    int32_t* __restrict__ rowsum_x, long long* __restrict__ colsum_xq, int rows_per_block, int multi_chunk,
+    int32_t* __restrict__ rowsum_x, long long* __restrict__ colsum_xq, int rows_per_block, int chunks,
     uint32_t* status)
 {
+    const int multi_chunk = chunks > 1;
+    const int chunk = (int)(blockIdx.x % (unsigned)chunks);
+    const int64_t slice = blockIdx.x / (unsigned)chunks;
     __shared__ int lds_rs[kQaMaxRows][kQaWaves];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int rsub = lane >> 3, c8 = lane & 7;
-    const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+    const int64_t r0 = slice * rows_per_block;
     const int nrows = (int)min((int64_t)rows_per_block, T - r0);
     const int64_t np = panel_count(K);
     const ActParams p = act_params(act_step, act_zero, F16);
 
-    const int64_t panel0 = (int64_t)blockIdx.x * kQaPanels + wave * kQaVpt;
+    const int64_t panel0 = (int64_t)chunk * kQaPanels + wave * kQaVpt;
     const int col0 = (int)(panel0 * kPanel) + c8 * 8;                      // K <= 2^31 - 1 columns
     int8_t* const dst0 = xq + (panel0 * T + r0) * kPanel + c8 * 8;         // this lane's 8 bytes of row r0, panel j = 0
     const int64_t dst_step = T * kPanel;                                   // to the next panel
@@ -254,18 +258,18 @@ int launch_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t
     rpb = cdiv(rpb, kQaRowsPerIter) * kQaRowsPerIter;
     if (rpb > kQaMaxRows) rpb = kQaMaxRows;
     slices = cdiv(T, rpb);
-    if (slices > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+    if (slices * chunks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
     const int multi = chunks > 1;
     // the accumulating outputs start from zero (a fill kernel, so the call can be graph-captured)
     if (colsum_xq) zero_fill_u32<<<(unsigned)cdiv(2 * K, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_xq), 2 * K);
     if (rowsum_x && multi) zero_fill_u32<<<(unsigned)cdiv(T, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(rowsum_x), T);
-    dim3 grid(chunks, (unsigned)slices);
+    const unsigned grid = (unsigned)(slices * chunks);
     if (dt == AWEQ_F16)
         quant_act_kernel<true><<<grid, kQaBlock, 0, st>>>(X, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x,
-                                                          reinterpret_cast<long long*>(colsum_xq), (int)rpb, multi, status);
+                                                          reinterpret_cast<long long*>(colsum_xq), (int)rpb, chunks, status);
     else
         quant_act_kernel<false><<<grid, kQaBlock, 0, st>>>(X, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x,
-                                                           reinterpret_cast<long long*>(colsum_xq), (int)rpb, multi, status);
+                                                           reinterpret_cast<long long*>(colsum_xq), (int)rpb, chunks, status);
     return launch_status();
 }
 
