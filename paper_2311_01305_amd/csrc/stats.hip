@@ -26,7 +26,7 @@ inline StatsPlan stats_plan(int64_t rows, int64_t K, int elts_per_lane)
     StatsPlan p;
     const int64_t cols_per_block = (int64_t)kWave * elts_per_lane;
     p.col_chunks = (int)cdiv(K, cols_per_block);
-    int64_t want = cdiv(2560, p.col_chunks);           // ~10 blocks per compute unit (5 resident)
+    int64_t want = cdiv(1280, p.col_chunks);           // 5 blocks per compute unit, all resident: fewer partial rows to merge
     int64_t max_slices = cdiv(rows, kStatsWaves * kRowBatch);  // at least one row batch per wavefront
     if (want > max_slices) want = max_slices;
     if (want < 1) want = 1;
