@@ -25,9 +25,9 @@ F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, published
 # on this workload (profiles/gemm_i8_fast_opt6.7b_hbm_traffic.txt), scaled by what the same
 # counters read for a plain 1 GiB device copy (FETCH x2.0, WRITE x1.0).  Keyed by (N, K), T = 262144.
 GEMM_TRAFFIC_BYTES = {
-    (4096, 4096): (6.77e9, 4.57e9),
-    (16384, 4096): (26.5e9, 18.3e9),
-    (4096, 16384): (26.9e9, 4.56e9),
+    (4096, 4096): (6.79e9, 4.57e9),
+    (16384, 4096): (26.0e9, 18.3e9),
+    (4096, 16384): (29.1e9, 4.56e9),
 }
 
 
