@@ -36,12 +36,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--cfg", type=int, default=2, help="workload (BASELINE.json configs index + 1); 2 = OPT-6.7B block")
+    ap.add_argument("--cfg", type=int, default=2, help="workload number (1 single 512x512 layer, 2 OPT-6.7B block, 3 LLaMA-7B block, 5 LLaMA-65B block)")
     ap.add_argument("--tokens", type=int, default=0, help="override the number of calibration tokens (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--out-deq", action="store_true", help="GEMM writes the de-quantised fp16 output instead of int32")
     ap.add_argument("--weight-only", type=int, default=0, choices=(0, 3, 4),
-                    help="weight-only calibration (BASELINE.json configs[3]): W4 or W3 per group of 128, fp16 activations "
+                    help="weight-only calibration (workload 4, LLaMA-7B shapes): W4 or W3 per group of 128, fp16 activations "
                          "(statistics, equalization, weight quantizer, bias correction; no GEMM); implies --cfg 4")
     ap.add_argument("--block", action="store_true",
                     help="run the block with its real data flow: linears that read the same activation (q/k/v, gate/up) "

@@ -1,4 +1,4 @@
-"""The layer shapes of every BASELINE.json configuration (LLaMA-7B, weight-only W4 / W3,
+"""The layer shapes of every benchmark configuration (LLaMA-7B, weight-only W4 / W3,
 LLaMA-65B) through the whole GPU path, at their real K and N and a reduced number of
 calibration tokens, against the oracle.  The integer stages are compared with the oracle fed
 the GPU's own fp32 scales (bit-exact given identical scales); scales to 1e-5."""
