@@ -150,7 +150,7 @@ def block_bench(args, torch, B, pipeline, synth, dev):
 
 
 def weight_only_bench(args, torch, B, pipeline, synth, dev):
-    """configs[3]: every linear of the LLaMA-7B-shaped block through statistics, equalization,
+    """Workload 4 (weight-only): every linear of the LLaMA-7B-shaped block through statistics, equalization,
     the W4 / W3 group-128 weight quantizer and the weight-only bias correction."""
     wl = synth.WORKLOADS[4]
     T = args.tokens or wl.T
