@@ -157,4 +157,15 @@ __device__ __forceinline__ f16x2 hmin2(f16x2 a, f16x2 b) { return __builtin_elem
 __device__ __forceinline__ f16x2 hmax2(f16x2 a, f16x2 b) { return __builtin_elementwise_max(a, b); }
 struct alignas(16) Float4 { float f[4]; };
 
+// An fp32 result that is about to be rounded to binary16.  hipcc merges an fp32 multiply and the
+// conversion of its product into one v_fma_mixlo_f16, and that instruction rounds the exact
+// product once; Eq. 3's fold is defined with two roundings (fp32 product, then the weight's
+// type), which differ in about one element per 10^7.  Passing the product through a register
+// the compiler cannot see into keeps the two steps apart.
+__device__ __forceinline__ float rounded_f32(float v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 }  // namespace aweq

@@ -77,8 +77,8 @@ __global__ __launch_bounds__(256) void fold_weight(const void* __restrict__ Wv, 
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 float2 f = h2f2(v.h[i]);
-                f.x = f.x * sc[2 * i];
-                f.y = f.y * sc[2 * i + 1];
+                f.x = rounded_f32(f.x * sc[2 * i]);
+                f.y = rounded_f32(f.y * sc[2 * i + 1]);
                 o.h[i] = f16x2{(_Float16)f.x, (_Float16)f.y};
             }
             *reinterpret_cast<Half8*>(O + n * ldw + col) = o;

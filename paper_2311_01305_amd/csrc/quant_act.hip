@@ -12,6 +12,15 @@
 // while the second correction's error is below (1/2 + 2^-22) beta 2^-24 ulp, which is
 // smaller whenever beta <= 1 - 2^-20.  Steps with a significand above that, exponents
 // outside [-60, 60], zero points beyond 2^23 and binary32 inputs take the true division.
+//
+// That sequence is still 6 of the 13 operations an element costs, and it only matters next to a
+// rounding tie.  So the common case is screened: q' = RN(a y + Z) in one FMA, n' = rint(q').
+// With Q = a / Step, the value the definition rounds is v = RN(Q) + Z, and
+//   |q' - v| <= |Q| 2^-23 + ulp(q') / 2  <=  (257 + |Z|) 2^-23 + 2^-16   wherever n' is in [-1, 256],
+// so if q' is farther than delta = (258 + |Z|) 2^-23 + 2^-15 from every half-integer, v lies in
+// the same unit interval and rint(RN(Q)) + Z = n' (outside [-1, 256] the relative error 2^-22
+// keeps both on the same side of the clamp).  Units of 8 values with an element inside delta
+// (about 1.5e-4 of all elements for |Z| <= 255) are redone with the exact sequence.
 #include "common.hpp"
 #include <type_traits>
 
@@ -26,9 +35,9 @@ constexpr int kQaRowBatch = 4;                          // groups of 8 rows in f
 constexpr int kQaRowsPerIter = 8 * kQaRowBatch;
 
 struct ActParams {
-    float step, rstep, lo_f, hi_f;
+    float step, rstep, lo_f, hi_f, thr;
     int zero, zoff;
-    bool fast;
+    bool fast, screen;
 };
 
 __device__ __forceinline__ ActParams act_params(const float* act_step, const int32_t* act_zero, bool f16)
@@ -41,6 +50,10 @@ __device__ __forceinline__ ActParams act_params(const float* act_step, const int
     const int e = (int)((b >> 23) & 0xff) - 127;
     const uint32_t m = b & 0x7fffffu;
     p.fast = f16 && (b >> 31) == 0 && e >= -60 && e <= 60 && m < 0x7ffff0u && p.zero > -(1 << 23) && p.zero < (1 << 23);
+    // screened quotient: |Z| small enough for delta to stay far below 1/2
+    const int az = p.zero < 0 ? -p.zero : p.zero;
+    p.screen = p.fast && az <= 4096;
+    p.thr = 0.5f - ((float)(258 + (az <= 4096 ? az : 0)) * 1.1920928955078125e-07f + 3.0517578125e-05f);
     p.lo_f = (float)(-p.zero);
     p.hi_f = (float)(255 - p.zero);
     p.zoff = p.zero - 128;
@@ -52,12 +65,46 @@ __device__ __forceinline__ ActParams act_params(const float* act_step, const int
 // with v_cvt_pk_u8_f32 and turned into the stored signed code by flipping the top bit
 // (u - 128 = u ^ 0x80 as a byte).  Column sums accumulate u in fp32 (exact: at most 512 rows
 // of values <= 255 per block); the caller subtracts 128 per row afterwards.
-template <bool FAST>
+// MODE 0: true division; 1: the exact division-free quotient; 2: screened (see the header).
+template <int MODE>
 __device__ __forceinline__ void act_unit(const float x[8], const float is[8], const ActParams& p, int8_t* dst,
                                          float csf[8], int csi[8], int& rs, float& big, uint32_t& st)
 {
     uint32_t w[2] = {0u, 0u};
-    if constexpr (FAST) {
+    if constexpr (MODE == 2) {
+        const float zf = (float)p.zero;
+        float n[8];
+        float dmax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            // x is a widened binary16 value: a = RN(x inv_s) as one mixed-precision FMA (+0 changes
+            // nothing but the sign of a zero, which the quotient's rounding forgets)
+            const float a = __builtin_fmaf(x[i], is[i], 0.0f);
+            const float q = __builtin_fmaf(a, p.rstep, zf);
+            n[i] = rintf(q);
+            dmax = fmaxf(dmax, fabsf(q - n[i]));
+        }
+        if (dmax > p.thr) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float a = x[i] * is[i];
+                float q = a * p.rstep;
+                float r = __builtin_fmaf(-p.step, q, a);
+                q = __builtin_fmaf(r, p.rstep, q);
+                r = __builtin_fmaf(-p.step, q, a);
+                q = __builtin_fmaf(r, p.rstep, q);
+                n[i] = rintf(q) + zf;   // |rint| < 2^24 here (checked per thread), |Z| <= 4096
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float u = __builtin_amdgcn_fmed3f(n[i], 0.0f, 255.0f);
+            csf[i] += u;
+            w[i >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(u, i & 3, w[i >> 2]);
+        }
+        w[0] ^= 0x80808080u;
+        w[1] ^= 0x80808080u;
+    } else if constexpr (MODE == 1) {
         const float zf = (float)p.zero;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -154,6 +201,7 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     bool valid[kQaVpt], pad[kQaVpt];
     float is[kQaVpt][8];
     bool fast_thread = p.fast;
+    float is_max = 0.0f;
 #pragma unroll
     for (int j = 0; j < kQaVpt; ++j) {
         valid[j] = col0 + j * kPanel < K;
@@ -163,10 +211,15 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
             is[j][i] = valid[j] ? inv_s[col0 + j * kPanel + i] : 1.0f;
             // the exactness argument needs a y not to overflow: binary16 |x| < 2^16, Step >= 2^-60
             if (!(fabsf(is[j][i]) < 1.0e12f)) fast_thread = false;
+            is_max = fmaxf(is_max, fabsf(is[j][i]));
         }
     }
+    // the screened path does not track the largest quotient: it needs |x inv_s / Step| < 2^24
+    // for every binary16 x up front (65504 max|inv_s| / Step with a margin for the roundings)
+    const bool screen_thread = fast_thread && p.screen && 65600.0f * is_max * p.rstep < 16777216.0f;
     // one path for the whole block (the choice is uniform unless an inv_s is absurd)
     const bool fast = __syncthreads_and(fast_thread ? 1 : 0) != 0;
+    const bool screen = __syncthreads_and(screen_thread ? 1 : 0) != 0;
     uint32_t st = 0;
     float big = 0.0f;
     float csf[kQaVpt][8];
@@ -177,8 +230,8 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
         for (int i = 0; i < 8; ++i) { csf[j][i] = 0.0f; csi[j][i] = 0; }
     int my_rows = 0;
 
-    auto rows_loop = [&](auto fast_c) {
-        constexpr bool FAST = decltype(fast_c)::value;
+    auto rows_loop = [&](auto mode_c) {
+        constexpr int MODE = decltype(mode_c)::value;
         for (int rb = 0; rb < nrows; rb += kQaRowsPerIter) {
             RawUnit<F16> raw[kQaRowBatch][kQaVpt];
 #pragma unroll
@@ -201,7 +254,7 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
                         if (valid[j]) {
                             float x[8];
                             raw[b][j].get(x);
-                            act_unit<FAST>(x, is[j], p, d, csf[j], csi[j], rs, big, st);
+                            act_unit<MODE>(x, is[j], p, d, csf[j], csi[j], rs, big, st);
                         } else if (pad[j]) {
                             *reinterpret_cast<uint2*>(d) = make_uint2(0u, 0u);
                         }
@@ -212,8 +265,13 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
             }
         }
     };
-    if (fast) rows_loop(std::true_type{});
-    else rows_loop(std::false_type{});
+    if constexpr (F16) {
+        if (screen) rows_loop(std::integral_constant<int, 2>{});
+        else if (fast) rows_loop(std::integral_constant<int, 1>{});
+        else rows_loop(std::integral_constant<int, 0>{});
+    } else {
+        rows_loop(std::integral_constant<int, 0>{});   // binary32 input: the true division
+    }
     if (big >= 16777216.0f) st |= AWEQ_ST_BIGQUOT;
     raise_status(status, st);
 

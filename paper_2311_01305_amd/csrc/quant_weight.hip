@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kQwBlock) void quant_weight_row(
                 reg[j].get(x);
                 const Float4 s0 = *reinterpret_cast<const Float4*>(s + u * 8), s1 = *reinterpret_cast<const Float4*>(s + u * 8 + 4);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { x[i] = x[i] * s0.f[i]; x[4 + i] = x[4 + i] * s1.f[i]; }
+                for (int i = 0; i < 4; ++i) { x[i] = rounded_f32(x[i] * s0.f[i]); x[4 + i] = rounded_f32(x[4 + i] * s1.f[i]); }
                 reg[j].set(x);
                 reg[j].store(reinterpret_cast<char*>(W_hat) + (size_t)n * ldwh * (F16 ? 2 : 4), u);
             }

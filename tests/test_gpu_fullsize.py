@@ -1,6 +1,8 @@
-"""Parity at the full size and in the launch configuration bench.py times: one linear of the
-OPT-6.7B-shaped block (T = 262144 calibration tokens, 4096 x 4096, fp16) run through the whole
-path on the GPU with the same driver the benchmark uses.
+"""Parity at the full size and in the launch configuration bench.py times: linears of the
+OPT-6.7B-shaped block (q_proj: T = 262144 calibration tokens, 4096 x 4096, fp16) and of the
+LLaMA-7B-shaped block (down_proj: 4096 x 11008, heavy-tailed activations, three ragged column
+chunks in the activation quantizer, 172 K-panels in the GEMM) run through the whole path on the
+GPU with the same driver the benchmark uses.
 
 The streaming stages are checked against the oracle over the FULL input (statistics, and the
 activation quantizer's codes through its exact column / row sums); the int32 GEMM output on
@@ -22,20 +24,21 @@ def progress(msg):
     print(f"[gpu-fullsize] {msg}", flush=True)
 
 
-@pytest.fixture(scope="module")
-def run():
+@pytest.fixture(scope="module", params=[(2, 0), (3, 6)], ids=["opt6.7b-q_proj", "llama7b-down_proj"])
+def run(request):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from paper_2311_01305_amd import binding, pipeline, synth
     binding.load_library()
-    cfg, li = 2, 0
+    cfg, li = request.param
     wl = synth.WORKLOADS[cfg]
     lin = wl.linears[li]
     seed = synth.layer_seed(cfg, li)
     progress(f"generating {lin.name} X[{wl.T} x {lin.K}] on the device")
     X = synth.make_act_torch(seed, wl.T, lin.K, wl, DEV)
     W = synth.make_weight_torch(seed, lin.N, lin.K, wl.dtype, DEV)
-    b = torch.from_numpy(synth.make_bias_np(seed, lin.N, wl.has_bias)).to(DEV)
+    b_np = synth.make_bias_np(seed, lin.N, wl.has_bias)
+    b = None if b_np is None else torch.from_numpy(b_np).to(DEV)
     buf = pipeline.LayerBuffers(wl.T, lin.K, lin.N, torch.float16, want_out_i32=True, want_out_deq=False, device=DEV)
     progress("running the whole path")
     t = pipeline.calibrate_layer(X, W, b, buf, fused_weight_pass=True)  # the call sequence bench.py times
@@ -149,6 +152,6 @@ def test_fullsize_bias_correction(run, orc):
     progress("bias correction")
     d_ref, b_ref = orc.bias_w8a8(h(t["W_hat"]), h(t["mu_xhat"]), wl.T, h(t["colsum_acc"]), h(t["colsum_xq"]),
                                  h(t["rowsum_w"]), h(t["act_step"])[0], int(h(t["act_zero"])[0]), h(t["step_w"]),
-                                 h(t["zero_w"]), h(run["b"]))
+                                 h(t["zero_w"]), None if run["b"] is None else h(run["b"]))
     assert np.max(np.abs(h(t["delta"]) - d_ref)) <= 1e-5 * np.max(np.abs(d_ref))
     np.testing.assert_allclose(h(t["bias_out"]), b_ref, rtol=1e-5, atol=1e-5 * np.max(np.abs(d_ref)))

@@ -288,6 +288,52 @@ def test_fold_quant_weight_equals_two_calls(B, orc, dtype, N, K, bits):
     assert np.array_equal(host(Wd).view(np.uint8), Wh.view(np.uint8)) and np.array_equal(host(zero), o["zero"])
 
 
+def double_rounding_pairs(rng, count, want_up):
+    """(w binary16, s binary32) pairs whose product rounds differently in one step (exact -> binary16)
+    than in the two steps of the fold (exact -> binary32 -> binary16); want_up: single > double."""
+    out = []
+    while len(out) < count:
+        w = rng.uniform(0.5, 1.0, 400000).astype(np.float16)
+        s = rng.uniform(16.0, 32.0, w.size).astype(np.float32)
+        two = (w.astype(np.float32) * s).astype(np.float16)
+        one = (w.astype(np.float64) * s.astype(np.float64)).astype(np.float16)
+        pick = np.nonzero((one > two) if want_up else (one < two))[0]
+        out += [(w[i], s[i]) for i in pick]
+    return out[:count]
+
+
+def test_fold_rounds_twice_at_the_row_extremes(B, orc):
+    """Eq. 3's fold is an fp32 product rounded to the weight's type.  Each row here has its
+    maximum (even rows) or minimum (odd rows) on an element where rounding the exact product
+    once gives the neighbouring binary16 value: Step, Z and the codes must follow the
+    twice-rounded W_hat that is stored."""
+    progress("fold double rounding at the row extremes (fused fold + quantizer)")
+    rng = np.random.default_rng(99)
+    N, K = 16, 1024
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    s = rng.uniform(0.5, 2.0, K).astype(np.float32)
+    up, down = double_rounding_pairs(rng, N // 2, True), double_rounding_pairs(rng, N // 2, False)
+    for n in range(N):
+        w, sv = (up if n % 2 == 0 else down)[n // 2]
+        col = 8 * n + 3
+        s[col] = sv
+        W[:, col] = 0
+        W[n, col] = w if n % 2 == 0 else -w          # negated: the minimum, with single < double
+    Wh = orc.fold_weight(W, s)
+    one = (W.astype(np.float64) * s.astype(np.float64)).astype(np.float16)
+    assert np.count_nonzero(one != Wh) >= N and all(Wh[n].argmax() == 8 * n + 3 for n in range(0, N, 2))
+    o = orc.quant_weight(Wh, 8, 0)
+    codes = torch.full((B.aweq_panel_bytes(N, K),), 0x5a, dtype=torch.uint8, device=DEV)
+    step, zero, rowsum = e(N, dtype=torch.float32), e(N, dtype=torch.int32), e(N, dtype=torch.int32)
+    W_hat = torch.zeros((N, K), dtype=torch.float16, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    B.aweq_fold_quant_weight(dev(W), B.AWEQ_F16, N, K, K, dev(s), W_hat, 8, codes, step, zero, rowsum, status)
+    assert np.array_equal(host(W_hat).view(np.uint16), Wh.view(np.uint16))
+    assert np.array_equal(host(step), o["step"]) and np.array_equal(host(zero), o["zero"])
+    assert np.array_equal(from_panels(host(codes), N, K).reshape(-1), orc.pack_codes(o["codes_u"], 8).view(np.uint8).reshape(-1))
+    assert np.array_equal(host(rowsum), o["rowsum_w"])
+
+
 # ------------------------------------------------------------------------------ stage 4a
 
 
@@ -361,6 +407,34 @@ def test_quant_act_quotient_paths(B, orc):
     Xo[6] = -60000
     o = check_quant_act(B, orc, Xo, inv_s, np.float32(0.02), 128)
     assert o["xq"][5].max() == 127 and o["xq"][6].min() == -128
+
+
+def test_quant_act_screened_near_ties(B, orc):
+    """The screened quotient decides from one FMA unless a value is close to a rounding tie; then
+    the unit is redone exactly.  Here every column has its inv_s tuned so that x inv_s / Step lands
+    within a few binary32 ulps of a tie (both sides and exactly on it), for small, negative, large
+    and too-large zero points."""
+    progress("quant_act screened quotient next to ties")
+    rng = np.random.default_rng(4242)
+    T, K = 40, 1024
+    mult = np.array([1, 3, 5, -1, -3], np.float64)
+    for sp, zero in ((0.037, 128), (0.5, 0), (1.0 / 3.0, 255), (0.0123, -300), (0.21, 4000), (0.21, 4097),
+                     (7.3e-3, 77), (1.9990234375, 130)):
+        sp = np.float32(sp)
+        xk = (rng.integers(8, 129, K) / 16.0)                      # few significand bits: 3 x, 5 x exact in binary16
+        m = rng.integers(-zero - 2, 258 - zero, K).astype(np.float64)
+        target = (m + 0.5) * np.float64(sp) / xk
+        inv_s = target.astype(np.float32)
+        for _ in range(3):                                         # 0 .. 3 ulps to either side
+            up = rng.random(K) < 0.5
+            moved = np.where(up, np.nextafter(inv_s, np.float32(np.inf)), np.nextafter(inv_s, np.float32(-np.inf)))
+            inv_s = np.where(rng.random(K) < 0.6, moved, inv_s).astype(np.float32)
+        inv_s = np.where(np.abs(inv_s) > 1e-6, inv_s, np.float32(1.0)).astype(np.float32)
+        X = (rng.standard_normal((T, K)) * 2).astype(np.float16)
+        for r, c in enumerate(mult):
+            X[r] = (xk * c).astype(np.float16)
+            assert np.array_equal(X[r].astype(np.float64), xk * c)
+        check_quant_act(B, orc, X, inv_s, sp, zero)
 
 
 def test_panel_converters(B):

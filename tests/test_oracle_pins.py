@@ -160,6 +160,25 @@ def test_scale_guards(orc):
     assert s[4] == 1.0
 
 
+def test_fold_rounds_in_two_steps(orc):
+    """The folded binary16 weight is the fp32 product rounded to binary16 (Sec. 3.1, Eq. 3, with
+    the model stored as FP16, Sec. 2): two roundings.  Special case that reduces to a library
+    routine: numpy's float32 multiply followed by its float16 cast.  The inputs are pairs found
+    by search for which rounding the exact product once gives the other binary16 neighbour, so
+    the pin tells the two readings apart."""
+    # a searched pair where the two routes differ, so that the pin can tell them apart
+    rng = np.random.default_rng(5)
+    wv = rng.uniform(0.5, 1.0, 200000).astype(np.float16)
+    sv = rng.uniform(16.0, 32.0, wv.size).astype(np.float32)
+    two = (wv.astype(np.float32) * sv).astype(np.float16)
+    one = (wv.astype(np.float64) * sv.astype(np.float64)).astype(np.float16)
+    d = np.nonzero(one != two)[0]
+    assert d.size > 0
+    got = np.array([orc.fold_weight(np.array([[wv[i]]], np.float16), np.array([sv[i]], np.float32))[0, 0] for i in d[:20]])
+    assert np.array_equal(got.view(np.uint16), two[d[:20]].view(np.uint16))
+    assert not np.array_equal(got.view(np.uint16), one[d[:20]].view(np.uint16))
+
+
 @pytest.mark.parametrize("dt,tol", [(np.float32, 2e-6), (np.float16, 2e-3)])
 def test_fold_leaves_product_unchanged(orc, dt, tol):
     """Eq. 3: (X diag(s)^-1)(diag(s) W) = X W."""
