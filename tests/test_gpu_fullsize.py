@@ -1,8 +1,9 @@
 """Parity at the full size and in the launch configuration bench.py times: linears of the
 OPT-6.7B-shaped block (q_proj: T = 262144 calibration tokens, 4096 x 4096, fp16) and of the
 LLaMA-7B-shaped block (down_proj: 4096 x 11008, heavy-tailed activations, three ragged column
-chunks in the activation quantizer, 172 K-panels in the GEMM) run through the whole path on the
-GPU with the same driver the benchmark uses.
+chunks in the activation quantizer, 172 K-panels in the GEMM) and of the LLaMA-65B-shaped block
+(gate_proj: 22016 x 8192, 86 output-tile columns, 23 GB of int32 output) run through the whole
+path on the GPU with the same driver the benchmark uses.
 
 The streaming stages are checked against the oracle over the FULL input (statistics, and the
 activation quantizer's codes through its exact column / row sums); the int32 GEMM output on
@@ -24,7 +25,7 @@ def progress(msg):
     print(f"[gpu-fullsize] {msg}", flush=True)
 
 
-@pytest.fixture(scope="module", params=[(2, 0), (3, 6)], ids=["opt6.7b-q_proj", "llama7b-down_proj"])
+@pytest.fixture(scope="module", params=[(2, 0), (3, 6), (5, 4)], ids=["opt6.7b-q_proj", "llama7b-down_proj", "llama65b-gate_proj"])
 def run(request):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
