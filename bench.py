@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--layers", default="", help="comma-separated layer names to keep (profiling runs)")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="only measure the sustained shader clock / MFMA rate for three kinds of operand data and exit")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="context, not the product: time the ROCm library's int8 GEMM (torch._int_mm) and fp16 GEMM on "
+                         "the operands one calibrated layer produces, next to aweq_w8a8_gemm / aweq_wonly_gemm")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="only run a plain device copy of this many bytes (reference for the HBM counters) and exit")
     return ap.parse_args()
@@ -288,6 +291,69 @@ def mfma_probe(torch, B, dev, iters=20000, reps=12):
     return {"mfma_probe": res, "compute_units": cus}
 
 
+def library_gemm(args, torch, B, pipeline, synth, dev):
+    """The vendor library's GEMMs on the same operands and the same box, as context for the
+    rooflines: int8 (torch._int_mm) against aweq_w8a8_gemm on the codes a calibrated layer
+    produces, fp16 (torch.matmul) against aweq_wonly_gemm.  Nothing of the product runs through
+    the library; this only says what its tuned kernels reach here."""
+    wl = synth.WORKLOADS[args.cfg]
+    T = args.tokens or wl.T
+    keep = set(x for x in args.layers.split(",") if x) or {wl.linears[0].name}
+    out = []
+
+    def timed(fn, n=10, w=4):
+        for _ in range(w):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in ev)
+        return ts[len(ts) // 2]
+
+    for li, lin in enumerate(wl.linears):
+        if lin.name not in keep:
+            continue
+        seed = synth.layer_seed(wl.cfg, li)
+        X = synth.make_act_torch(seed, T, lin.K, wl, dev)
+        W = synth.make_weight_torch(seed, lin.N, lin.K, wl.dtype, dev)
+        buf = pipeline.LayerBuffers(T, lin.K, lin.N, torch.float16, device=dev)
+        t = pipeline.calibrate_layer(X, W, None, buf, fused_weight_pass=True)
+        torch.cuda.synchronize()
+        K, N = lin.K, lin.N
+        ops = 2.0 * T * N * K
+        ours = timed(lambda: B.aweq_w8a8_gemm(t["xq"], B.AWEQ_I8, T, K, K, None, None, None, None, None, None, t["codes"], N,
+                                              None, None, None, None, t["out_i32"], None, B.AWEQ_F16, N, None, None))
+        ours_cs = timed(lambda: B.aweq_w8a8_gemm(t["xq"], B.AWEQ_I8, T, K, K, None, None, None, None, None, None, t["codes"], N,
+                                                 None, None, None, None, t["out_i32"], None, B.AWEQ_F16, N, t["colsum_acc"], None))
+        xq_rm = torch.empty((T, K), dtype=torch.int8, device=dev)
+        wq_rm = torch.empty((N, K), dtype=torch.int8, device=dev)
+        B.aweq_unpack_panels_i8(t["xq"], T, K, xq_rm, K)
+        B.aweq_unpack_panels_i8(t["codes"], N, K, wq_rm, K)
+        ref_out = t["out_i32"].clone()
+        lib_ms = timed(lambda: torch._int_mm(xq_rm, wq_rm.t(), out=t["out_i32"]))
+        same = bool(torch.equal(ref_out, t["out_i32"]))
+        del ref_out, xq_rm, wq_rm
+        # fp16: the library on X and the folded weight, ours on W4 codes of the same weight
+        y = torch.empty((T, N), dtype=torch.float16, device=dev)
+        lib_h = timed(lambda: torch.matmul(X, t["W_hat"].t(), out=y))
+        bw = pipeline.LayerBuffers(T, K, N, torch.float16, bits=4, group=128, w8a8=False, device=dev)
+        tw = pipeline.calibrate_layer(X, W, None, bw)
+        ws = torch.empty(B.aweq_workspace_size(B.OP_WONLY_GEMM, T, K, N), dtype=torch.uint8, device=dev)
+        ours_h = timed(lambda: B.aweq_wonly_gemm(X, T, K, K, tw["codes"], 4, 128, tw["step_w"], tw["zero_w"], N, None, y,
+                                                 B.AWEQ_F16, N, ws))
+        out.append({"name": lin.name, "T": T, "N": N, "K": K,
+                    "int8_TOPs": {"aweq_w8a8_gemm_int32_out": ops / ours / 1e9, "aweq_w8a8_gemm_int32_out_colsum": ops / ours_cs / 1e9,
+                                  "library_int_mm": ops / lib_ms / 1e9, "outputs_identical": same},
+                    "fp16_TFLOPs": {"aweq_wonly_gemm_w4": ops / ours_h / 1e9, "library_matmul": ops / lib_h / 1e9}})
+        del X, W, buf, t, bw, tw, y, ws
+        torch.cuda.empty_cache()
+    return {"library_gemm": out, "workload": f"cfg{wl.cfg} {wl.name}"}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -306,6 +372,9 @@ def main():
     torch.cuda.set_device(0)
     if args.mfma_probe:
         print(json.dumps(mfma_probe(torch, B, dev)))
+        return
+    if args.library_gemm:
+        print(json.dumps(library_gemm(args, torch, B, pipeline, synth, dev)))
         return
     if args.copy_probe:
         # a plain copy kernel of known size: what FETCH_SIZE / WRITE_SIZE read for it gives the
