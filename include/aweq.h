@@ -175,6 +175,32 @@ int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t K, int64_t
                    int64_t* colsum_acc, void* ws, size_t ws_bytes,
                    uint32_t* status, void* stream);
 
+/* ---- Stage 4 with fused epilogues for the layer that consumes this one's output (statistics of
+ * Sec. 3.2 / Sec. 3.3's E[x] and the quantizer of Eq. 1 applied where the output is produced
+ * instead of in passes of their own over it).  The GEMM and the de-quantisation are those of
+ * aweq_w8a8_gemm with x_dt = I8; y[t,n] = act(de-quantised output + bias) rounded to binary16,
+ * act = 0 (none) or 1 (ReLU, OPT's fc1 -> fc2).  Outputs:
+ *  out_f16[T x N] (pitch ldo, nullable): y itself;
+ *  colsum_acc[N] (required): as in aweq_w8a8_gemm, for this layer's stage 5;
+ *  statistics (ycmin non-NULL): ycmin[N], ycmax[N], ycsum[N] (nullable), ycount[1] (nullable) =
+ *    what aweq_calib_stats(y, F16, rows = T, K = N, accumulate) returns on the stored output:
+ *    extremes exact, sums exact (integer accumulation in units of 2^-24), independent of the
+ *    launch; needs ws of aweq_workspace_size(AWEQ_OP_W8A8_GEMM, T, K, N) bytes;
+ *  next-layer codes (yq non-NULL): yq[T x N] in the K-panel layout (aweq_panel_bytes(T, N) bytes),
+ *    rowsum_y[T] (nullable), colsum_yq[N] (nullable) = what aweq_quant_act(y, F16, T, N, ...,
+ *    next_inv_s[N], next_step[1], next_zero[1]) returns (true division).
+ * At least one of the two.  Shapes the tiled kernel takes only: N % 4 == 0, 16-byte aligned
+ * vectors and outputs (AWEQ_ERR_SHAPE / AWEQ_ERR_ALIGN otherwise). */
+int aweq_w8a8_gemm_fused(const int8_t* xq, int64_t T, int64_t K, const int8_t* wq, int64_t N,
+                         const float* act_step, const int32_t* act_zero,
+                         const float* step_w, const int32_t* zero_w,
+                         const int32_t* rowsum_x, const int32_t* rowsum_w, const float* bias, int act,
+                         void* out_f16, int64_t ldo, int64_t* colsum_acc,
+                         float* ycmin, float* ycmax, double* ycsum, uint64_t* ycount, int accumulate,
+                         const float* next_inv_s, const float* next_step, const int32_t* next_zero,
+                         int8_t* yq, int32_t* rowsum_y, int64_t* colsum_yq,
+                         void* ws, size_t ws_bytes, uint32_t* status, void* stream);
+
 /* ---- Stage 5: quantization bias correction (Sec. 3.3, Eq. 11-15).
  * delta[n] = mean over the calibration tokens of the FP output of the equalised layer
  * minus the mean output of the quantised layer; bias_out = bias_in + delta (the paper

@@ -19,7 +19,7 @@ ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD = 1, 2, 4, 8
 
 EXPORTS = ("aweq_workspace_size", "aweq_status_string", "aweq_calib_stats", "aweq_equalize",
            "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock",
-           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8", "aweq_wonly_gemm", "aweq_fold_quant_weight")
+           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8", "aweq_wonly_gemm", "aweq_fold_quant_weight", "aweq_w8a8_gemm_fused")
 
 _vp, _i64, _i32, _u64, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_float, C.c_size_t
 
@@ -60,6 +60,9 @@ def load_library():
     lib.aweq_w8a8_gemm.restype = _i32
     lib.aweq_w8a8_gemm.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
                                    _vp, _vp, _vp, _vp, _i32, _i64, _vp, _vp, _sz, _vp, _vp]
+    lib.aweq_w8a8_gemm_fused.restype = _i32
+    lib.aweq_w8a8_gemm_fused.argtypes = [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i64, _vp,
+                                         _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp]
     lib.aweq_bias_correct.restype = _i32
     lib.aweq_bias_correct.argtypes = [_i32, _vp, _i32, _i64, _i64, _i64, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
@@ -177,6 +180,18 @@ def aweq_pack_panels_i8(src, rows, K, ld, panels, stream=None):
 
 def aweq_unpack_panels_i8(panels, rows, K, dst, ld, stream=None):
     _check(load_library().aweq_unpack_panels_i8(_ptr(panels), rows, K, _ptr(dst), ld, _stream(stream)))
+
+
+def aweq_w8a8_gemm_fused(xq, T, K, wq, N, act_step, act_zero, step_w, zero_w, rowsum_x, rowsum_w, bias, act, out_f16, ldo,
+                         colsum_acc, ycmin=None, ycmax=None, ycsum=None, ycount=None, accumulate=0, next_inv_s=None,
+                         next_step=None, next_zero=None, yq=None, rowsum_y=None, colsum_yq=None, ws=None, status=None,
+                         stream=None, ws_bytes=None):
+    _check(load_library().aweq_w8a8_gemm_fused(
+        _ptr(xq), T, K, _ptr(wq), N, _ptr(act_step), _ptr(act_zero), _ptr(step_w), _ptr(zero_w), _ptr(rowsum_x),
+        _ptr(rowsum_w), _ptr(bias), int(act), _ptr(out_f16), ldo, _ptr(colsum_acc), _ptr(ycmin), _ptr(ycmax), _ptr(ycsum),
+        _ptr(ycount), int(accumulate), _ptr(next_inv_s), _ptr(next_step), _ptr(next_zero), _ptr(yq), _ptr(rowsum_y),
+        _ptr(colsum_yq), _ptr(ws), (_nbytes(ws) if ws is not None else 0) if ws_bytes is None else ws_bytes, _ptr(status),
+        _stream(stream)))
 
 
 def aweq_wonly_gemm(X_hat, T, K, ldx, codes, bits, group, step_w, zero_w, N, bias, out, out_dt, ldo, ws,

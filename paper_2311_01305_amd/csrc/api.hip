@@ -12,8 +12,8 @@ extern "C" size_t aweq_workspace_size(aweq_op op, int64_t rows, int64_t K, int64
     case AWEQ_OP_CALIB_STATS: return aweq::stats_ws_bytes_export(rows, K);
     case AWEQ_OP_QUANT_WEIGHT: return 16;  // tensor-wide extremes for group = -1
     case AWEQ_OP_WONLY_GEMM: return N > 0 ? (size_t)N * (size_t)K * 2 : 0;  // the binary16 weight
+    case AWEQ_OP_W8A8_GEMM: return N > 0 ? (size_t)N * 16 : 0;  // aweq_w8a8_gemm_fused: keys and sums of the output statistics
     case AWEQ_OP_EQUALIZE:
-    case AWEQ_OP_W8A8_GEMM:
     case AWEQ_OP_BIAS_CORRECT:
     default: return 0;
     }

@@ -65,7 +65,29 @@ struct GemmArgs {
     const float* bias;
     int tiles_m, tiles_n, patch_m, patch_n, patches_n, n_patches;
     int n_ids;  // workgroup ids that may name a tile (whole rounds of patches over the XCDs)
+    // fused epilogues on the de-quantised binary16 output y (the next layer's calibration input)
+    int act;                    // 0: none, 1: ReLU before y is rounded
+    uint32_t* ykeys;            // [2 N] order-preserving keys of the column minimum / maximum of y
+    long long* yfix;            // [N] column sums of y in units of 2^-24 (exact: y is binary16)
+    const float* next_inv_s;    // [N] the next layer's 1 / s, Step and Z: y is quantised with them
+    const float* next_step;
+    const int32_t* next_zero;
+    int8_t* yq;                 // [T x N] codes of y, K-panel layout (panels of 64 output channels)
+    int32_t* rowsum_y;          // [T]
+    long long* colsum_yq;       // [N]
+    uint32_t* status;
 };
+
+// order-preserving unsigned key of a float (and back): integer atomics then find extremes
+__device__ __forceinline__ uint32_t ykey(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float ykey_float(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
 
 __global__ __launch_bounds__(kGemmThreads) void gemm_i8_generic(GemmArgs g)
 {
@@ -307,7 +329,9 @@ __device__ __forceinline__ bool tile_of(const GemmArgs& g, int vb, int& tile_m, 
 // (a multiple of 8), workgroup b takes the ids b, b + grid, b + 2 grid, ...; the first panels
 // of its next tile are requested before the epilogue of the current one starts, so the loads
 // fly while the results are stored.
-template <bool I32, int DEQ, bool COLSUM>
+// EPI (with DEQ == 2): bit 0 collects the column statistics of the binary16 output, bit 1 quantises
+// it for the next layer; STORE = false keeps the output itself from being written.
+template <bool I32, int DEQ, bool COLSUM, int EPI = 0, bool STORE = true>
 __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -374,7 +398,10 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
     // the output issues at least kStores stores per wave after requesting the next tile's first
     // three panels, so "at most kStores operations pending" means those panels have landed
     // while the stores may still be on their way (relaxed: set for the tile that follows).
-    constexpr int kStoresAll = (I32 ? 32 : 0) + (DEQ != 0 ? 32 : 0);   // 4 sub-tile rows x 8 passes each
+    static_assert(EPI == 0 || DEQ == 2, "the fused epilogues work on the binary16 output");
+    // 4 sub-tile rows x 8 passes each; the fused variants never take the relaxed wait (their
+    // atomics are not counted here)
+    constexpr int kStoresAll = EPI != 0 ? 0 : ((I32 ? 32 : 0) + (DEQ != 0 && STORE ? 32 : 0));
     constexpr int kStores = kStoresAll > 63 ? 63 : kStoresAll;
     bool relaxed = false;
 
@@ -515,6 +542,18 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
             zx = __builtin_amdgcn_readfirstlane(zx);
             sxf = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sxf)));
         }
+        Float4 nis = {{1.f, 1.f, 1.f, 1.f}};   // the next layer's 1 / s for this lane's four channels
+        float nstep = 1.0f;
+        int nzero = 0;
+        if constexpr ((EPI & 2) != 0) {
+            if (n_ok) nis = *reinterpret_cast<const Float4*>(g.next_inv_s + n);
+            nstep = *g.next_step;
+            nzero = *g.next_zero;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(nis.f[c]));
+            nstep = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(nstep)));
+            nzero = __builtin_amdgcn_readfirstlane(nzero);
+        }
 
         // next tile of this workgroup
         int nvb = vb + stride, ntm = 0, ntn = 0;
@@ -541,6 +580,12 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         const int wr_t = lane & 31;
         const int wr_sw = wr_t & 15, wr_half = lane >> 5;           // chunk (8 j + 2 q + l / 32) ^ (t & 15)
         long long csum[4] = {0, 0, 0, 0};
+        float ymn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, ymx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        double ysum[4] = {0.0, 0.0, 0.0, 0.0};   // exact: at most 128 binary16 values each
+        int cq[4] = {0, 0, 0, 0};                // column sums of the next layer's codes over this tile
+        uint32_t est = 0;
+        const bool yq_pad = (EPI & 2) != 0 && !n_ok && cn0 + wn * 64 < g.N;   // zero fill of the last panel
+        int8_t* const yq_lane = (EPI & 2) != 0 ? g.yq + (((cn0 >> 6) + wn) * g.T) * kPanel + rd_c * 4 : nullptr;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -556,6 +601,7 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                 const v4i o = *reinterpret_cast<const v4i*>(slab + r * 256 + ((rd_c ^ (r & 15)) * 16));
                 const int64_t t = t_lane + i * 32 + 4 * p;
                 unsigned rs = 0;
+                int rsy = 0;   // this lane's share of the token's code sum for the next layer
                 // row sum of token 32 i + 4 p + lane / 16 of the wave: held by lane (that % 64), half
                 // i / 2 (fetched with every lane active: a switched-off source lane would read as 0)
                 if constexpr (DEQ != 0) rs = (unsigned)__builtin_amdgcn_ds_bpermute((((i & 1) * 32 + 4 * p + rd_r) & 63) * 4, rsx[i >> 1]);
@@ -570,8 +616,35 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                         }
                         if constexpr (DEQ == 2) {
                             typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                            if constexpr (EPI != 0) {
+                                if (g.act == 1) {
+#pragma unroll
+                                    for (int c = 0; c < 4; ++c) y[c] = fmaxf(y[c], 0.0f);
+                                }
+                            }
                             h4 oh = {(_Float16)y[0], (_Float16)y[1], (_Float16)y[2], (_Float16)y[3]};
-                            __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out_deq) + t * g.ldo + n));
+                            if constexpr (STORE)
+                                __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out_deq) + t * g.ldo + n));
+                            if constexpr ((EPI & 1) != 0) {
+#pragma unroll
+                                for (int c = 0; c < 4; ++c) {
+                                    const float yf = (float)oh[c];
+                                    ymn[c] = fminf(ymn[c], yf);
+                                    ymx[c] = fmaxf(ymx[c], yf);
+                                    ysum[c] += (double)yf;
+                                }
+                            }
+                            if constexpr ((EPI & 2) != 0) {
+                                uint32_t w = 0;
+#pragma unroll
+                                for (int c = 0; c < 4; ++c) {
+                                    const int code = quant_div((float)oh[c] * nis.f[c], nstep, nzero, 255, est) - 128;
+                                    cq[c] += code;
+                                    rsy += code;
+                                    w |= (uint32_t)(code & 0xff) << (8 * c);
+                                }
+                                *reinterpret_cast<uint32_t*>(yq_lane + t * kPanel) = w;
+                            }
                         } else {
                             typedef float f4 __attribute__((ext_vector_type(4)));
                             f4 of = {y[0], y[1], y[2], y[3]};
@@ -582,9 +655,51 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
 #pragma unroll
                         for (int c = 0; c < 4; ++c) csum[c] += o[c];
                     }
+                } else if (yq_pad && t < g.T) {
+                    *reinterpret_cast<uint32_t*>(yq_lane + t * kPanel) = 0u;
+                }
+                if constexpr ((EPI & 2) != 0) {
+                    // the 16 lanes of one output row (every lane active here)
+                    rsy = group_allreduce<4>(rsy, OpAdd());
+                    if (rd_c == 0 && t < g.T && g.rowsum_y) atomicAdd(&g.rowsum_y[t], rsy);
                 }
             }
         }
+        if constexpr ((EPI & 1) != 0) {
+            // lanes l, l ^ 16, l ^ 32 hold the same channels for different tokens
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                ymn[c] = fminf(ymn[c], partner<4>(ymn[c]));
+                ymn[c] = fminf(ymn[c], partner<5>(ymn[c]));
+                ymx[c] = fmaxf(ymx[c], partner<4>(ymx[c]));
+                ymx[c] = fmaxf(ymx[c], partner<5>(ymx[c]));
+                ysum[c] += partner<4>(ysum[c]);
+                ysum[c] += partner<5>(ysum[c]);
+            }
+            if (lane < 16 && n_ok && ymn[0] <= ymx[0]) {   // (no token of this tile row was inside T: nothing to add)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    atomicMin(&g.ykeys[n + c], ykey(ymn[c]));
+                    atomicMax(&g.ykeys[g.N + n + c], ykey(ymx[c]));
+                    double f = ysum[c] * 16777216.0;   // an integer: binary16 values are multiples of 2^-24
+                    if (!(fabs(f) < 9.0e18)) { f = 0.0; est |= AWEQ_ST_NONFINITE; }
+                    atomicAdd(reinterpret_cast<unsigned long long*>(&g.yfix[n + c]), (unsigned long long)(long long)f);
+                }
+            }
+        }
+        if constexpr ((EPI & 2) != 0) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                cq[c] += partner<4>(cq[c]);
+                cq[c] += partner<5>(cq[c]);
+            }
+            if (lane < 16 && n_ok && g.colsum_yq) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    atomicAdd(reinterpret_cast<unsigned long long*>(&g.colsum_yq[n + c]), (unsigned long long)(long long)cq[c]);
+            }
+        }
+        if constexpr (EPI != 0) raise_status(g.status, est);
         if constexpr (COLSUM) {
             // lanes l, l ^ 16, l ^ 32 hold the same channels for different tokens
 #pragma unroll
@@ -629,6 +744,85 @@ int check_quant_act_args(const void* X, aweq_dtype dt, int64_t T, int64_t K, int
 
 using namespace aweq;
 
+namespace aweq {
+
+// tile / patch plan of a launch
+static int plan_gemm(GemmArgs& g, int64_t T, int64_t N, int64_t& blocks)
+{
+    const int64_t tiles_m = cdiv(T, BM), tiles_n = cdiv(N, BN);
+    if (tiles_m * tiles_n > (1ll << 30)) return AWEQ_ERR_SHAPE;
+    g.tiles_m = (int)tiles_m; g.tiles_n = (int)tiles_n;
+    // patch of output tiles an XCD works on at a time: 32 tiles (one per compute unit)
+    g.patch_n = (int)(tiles_n < 4 ? tiles_n : 4);
+    g.patch_m = 32 / g.patch_n;
+    if (g.patch_m > tiles_m) g.patch_m = (int)tiles_m;
+    g.patches_n = (int)cdiv(tiles_n, g.patch_n);
+    const int64_t patches_m = cdiv(tiles_m, g.patch_m);
+    g.n_patches = (int)(patches_m * g.patches_n);
+    const int64_t rounds = cdiv(g.n_patches, kXcds);
+    blocks = rounds * kXcds * g.patch_m * g.patch_n;
+    if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+    g.n_ids = (int)blocks;
+    return AWEQ_OK;
+}
+
+// persistent launch of a fast-kernel instantiation: one workgroup per compute unit (a multiple of
+// 8, so that id % 8 stays the XCD)
+static int launch_fast(const void* fn, GemmArgs& g, int64_t blocks, hipStream_t st)
+{
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, fast::kLds) != hipSuccess) return AWEQ_ERR_LAUNCH;
+    void* args[] = {&g};
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return AWEQ_ERR_LAUNCH;
+    int64_t grid = (cus / kXcds) * kXcds;
+    if (grid < kXcds) grid = kXcds;
+    if (grid > blocks) grid = blocks;
+    if (hipLaunchKernel(fn, dim3((unsigned)grid), dim3(fast::kThreads), args, fast::kLds, st) != hipSuccess) return AWEQ_ERR_LAUNCH;
+    return launch_status();
+}
+
+static void clear_fused(GemmArgs& g)
+{
+    g.act = 0; g.ykeys = nullptr; g.yfix = nullptr; g.next_inv_s = nullptr; g.next_step = nullptr; g.next_zero = nullptr;
+    g.yq = nullptr; g.rowsum_y = nullptr; g.colsum_yq = nullptr; g.status = nullptr;
+}
+
+// accumulators of the fused epilogues start from their identities (fill kernels: graph-capturable)
+__global__ void fused_init(uint32_t* ykeys, long long* yfix, int64_t N, long long* colsum_yq, int32_t* rowsum_y, int64_t T)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < N) {
+        if (ykeys) { ykeys[i] = 0xffffffffu; ykeys[N + i] = 0u; yfix[i] = 0; }
+        if (colsum_yq) colsum_yq[i] = 0;
+    }
+    if (rowsum_y && i < T) rowsum_y[i] = 0;
+}
+
+// keys / fixed-point sums -> the outputs aweq_calib_stats would give on the stored output
+__global__ void fused_stats_finish(const uint32_t* ykeys, const long long* yfix, int64_t N, int64_t T, float* cmin, float* cmax,
+                                   double* csum, uint64_t* count, int accumulate, uint32_t* status)
+{
+    const int64_t n = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (n == 0 && count) *count = (accumulate ? *count : 0) + (uint64_t)T;
+    if (n >= N) return;
+    float a = ykey_float(ykeys[n]), b = ykey_float(ykeys[N + n]);
+    double s = (double)yfix[n] * 5.9604644775390625e-08;   // 2^-24
+    if (isinf(a) || isinf(b)) raise_status(status, AWEQ_ST_NONFINITE);
+    if (accumulate) {
+        a = fminf(a, cmin[n]);
+        b = fmaxf(b, cmax[n]);
+        if (csum) s += csum[n];
+    }
+    cmin[n] = a;
+    cmax[n] = b;
+    if (csum) csum[n] = s;
+}
+
+}  // namespace aweq
+
+using namespace aweq;
+
 extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t K, int64_t ldx,
                               const float* inv_s, const float* act_step, const int32_t* act_zero,
                               int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
@@ -660,9 +854,6 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
         if (out_dt != AWEQ_F32 && out_dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
         if (!act_step || !act_zero || !step_w || !zero_w || !rowsum_x || !rowsum_w) return AWEQ_ERR_NULL;
     }
-    const int64_t tiles_m = cdiv(T, BM), tiles_n = cdiv(N, BN);
-    if (tiles_m * tiles_n > (1ll << 30)) return AWEQ_ERR_SHAPE;
-
     hipStream_t st = as_stream(stream);
     if (x_dt != AWEQ_I8) {
         const int rc = launch_quant_act(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, status, st);
@@ -676,18 +867,10 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     g.colsum_acc = reinterpret_cast<long long*>(colsum_acc);
     g.act_step = act_step; g.act_zero = act_zero; g.step_w = step_w; g.zero_w = zero_w;
     g.rowsum_x = rowsum_x; g.rowsum_w = rowsum_w; g.bias = bias;
-    g.tiles_m = (int)tiles_m; g.tiles_n = (int)tiles_n;
-    // patch of output tiles an XCD works on at a time: 32 tiles (one per compute unit)
-    g.patch_n = (int)(tiles_n < 4 ? tiles_n : 4);
-    g.patch_m = 32 / g.patch_n;
-    if (g.patch_m > tiles_m) g.patch_m = (int)tiles_m;
-    g.patches_n = (int)cdiv(tiles_n, g.patch_n);
-    const int64_t patches_m = cdiv(tiles_m, g.patch_m);
-    g.n_patches = (int)(patches_m * g.patches_n);
-    const int64_t rounds = cdiv(g.n_patches, kXcds);
-    const int64_t blocks = rounds * kXcds * g.patch_m * g.patch_n;
-    if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
-    g.n_ids = (int)blocks;
+    clear_fused(g);
+    int64_t blocks = 0;
+    const int prc = plan_gemm(g, T, N, blocks);
+    if (prc != AWEQ_OK) return prc;
 
     if (colsum_acc) zero_fill_u32_gemm<<<(unsigned)cdiv(2 * N, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_acc), 2 * N);
 
@@ -705,23 +888,74 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
         AWEQ_PICK(true, 1, true) AWEQ_PICK(true, 1, false) AWEQ_PICK(false, 1, true) AWEQ_PICK(false, 1, false)
         AWEQ_PICK(true, 2, true) AWEQ_PICK(true, 2, false) AWEQ_PICK(false, 2, true) AWEQ_PICK(false, 2, false)
 #undef AWEQ_PICK
-        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, fast::kLds) != hipSuccess) return AWEQ_ERR_LAUNCH;
-        void* args[] = {&g};
-        // persistent: one workgroup per compute unit (a multiple of 8, so that id % 8 stays the XCD)
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-            return AWEQ_ERR_LAUNCH;
-        int64_t grid = (cus / kXcds) * kXcds;
-        if (grid < kXcds) grid = kXcds;
-        if (grid > blocks) grid = blocks;
-        g.n_ids = (int)blocks;
-        if (hipLaunchKernel(fn, dim3((unsigned)grid), dim3(fast::kThreads), args, fast::kLds, st) != hipSuccess) return AWEQ_ERR_LAUNCH;
-        return launch_status();
+        return launch_fast(fn, g, blocks, st);
     }
     const size_t lds_bytes = 2 * 2 * kTileBytes;  // 64 KiB
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_generic), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds_bytes) != hipSuccess)
         return AWEQ_ERR_LAUNCH;
     gemm_i8_generic<<<(unsigned)blocks, kGemmThreads, lds_bytes, st>>>(g);
+    return launch_status();
+}
+
+extern "C" int aweq_w8a8_gemm_fused(const int8_t* xq, int64_t T, int64_t K, const int8_t* wq, int64_t N,
+                                    const float* act_step, const int32_t* act_zero,
+                                    const float* step_w, const int32_t* zero_w,
+                                    const int32_t* rowsum_x, const int32_t* rowsum_w, const float* bias, int act,
+                                    void* out_f16, int64_t ldo, int64_t* colsum_acc,
+                                    float* ycmin, float* ycmax, double* ycsum, uint64_t* ycount, int accumulate,
+                                    const float* next_inv_s, const float* next_step, const int32_t* next_zero,
+                                    int8_t* yq, int32_t* rowsum_y, int64_t* colsum_yq,
+                                    void* ws, size_t ws_bytes, uint32_t* status, void* stream)
+{
+    if (!xq || !wq || !act_step || !act_zero || !step_w || !zero_w || !rowsum_x || !rowsum_w || !colsum_acc) return AWEQ_ERR_NULL;
+    const bool want_stats = ycmin != nullptr, want_quant = yq != nullptr;
+    if (!want_stats && !want_quant) return AWEQ_ERR_NULL;
+    if (want_stats && !ycmax) return AWEQ_ERR_NULL;
+    if (want_quant && (!next_inv_s || !next_step || !next_zero)) return AWEQ_ERR_NULL;
+    if (act != 0 && act != 1) return AWEQ_ERR_SHAPE;
+    if (T <= 0 || N <= 0 || K <= 0 || (K % 8) != 0 || K > 32768 || (N % 4) != 0) return AWEQ_ERR_SHAPE;
+    if (out_f16 && (ldo < N || (ldo % 4) != 0)) return AWEQ_ERR_SHAPE;
+    if (!aligned16(xq) || !aligned16(wq) || !aligned16(step_w) || !aligned16(zero_w) || !aligned16(rowsum_w) ||
+        (bias && !aligned16(bias)) || (out_f16 && !aligned16(out_f16)) || (want_quant && (!aligned16(next_inv_s) || !aligned16(yq))))
+        return AWEQ_ERR_ALIGN;
+    if (want_stats && (!ws || ws_bytes < (size_t)N * 16)) return AWEQ_ERR_WORKSPACE;
+    if (want_stats && !aligned16(ws)) return AWEQ_ERR_ALIGN;
+
+    GemmArgs g;
+    g.A = xq; g.B = wq; g.T = T; g.N = N; g.K = K;
+    g.out_i32 = nullptr; g.out_deq = out_f16; g.out_f16 = 1; g.ldo = ldo;
+    g.colsum_acc = reinterpret_cast<long long*>(colsum_acc);
+    g.act_step = act_step; g.act_zero = act_zero; g.step_w = step_w; g.zero_w = zero_w;
+    g.rowsum_x = rowsum_x; g.rowsum_w = rowsum_w; g.bias = bias;
+    clear_fused(g);
+    g.act = act; g.status = status;
+    if (want_stats) {
+        g.yfix = reinterpret_cast<long long*>(ws);
+        g.ykeys = reinterpret_cast<uint32_t*>(g.yfix + N);
+    }
+    if (want_quant) {
+        g.next_inv_s = next_inv_s; g.next_step = next_step; g.next_zero = next_zero;
+        g.yq = yq; g.rowsum_y = rowsum_y; g.colsum_yq = reinterpret_cast<long long*>(colsum_yq);
+    }
+    int64_t blocks = 0;
+    const int prc = plan_gemm(g, T, N, blocks);
+    if (prc != AWEQ_OK) return prc;
+
+    hipStream_t st = as_stream(stream);
+    zero_fill_u32_gemm<<<(unsigned)cdiv(2 * N, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_acc), 2 * N);
+    const int64_t init_n = (want_quant && rowsum_y && T > N) ? T : N;
+    fused_init<<<(unsigned)cdiv(init_n, 256), 256, 0, st>>>(g.ykeys, g.yfix, N, want_quant ? g.colsum_yq : nullptr,
+                                                            want_quant ? rowsum_y : nullptr, T);
+    const int epi = (want_stats ? 1 : 0) | (want_quant ? 2 : 0);
+    const bool store = out_f16 != nullptr;
+    const void* fn = nullptr;
+#define AWEQ_PICK(E, S) if (epi == E && store == S) fn = reinterpret_cast<const void*>(fast::gemm_i8_fast<false, 2, true, E, S>);
+    AWEQ_PICK(1, true) AWEQ_PICK(1, false) AWEQ_PICK(2, true) AWEQ_PICK(2, false) AWEQ_PICK(3, true) AWEQ_PICK(3, false)
+#undef AWEQ_PICK
+    const int rc = launch_fast(fn, g, blocks, st);
+    if (rc != AWEQ_OK) return rc;
+    if (want_stats)
+        fused_stats_finish<<<(unsigned)cdiv(N, 256), 256, 0, st>>>(g.ykeys, g.yfix, N, T, ycmin, ycmax, ycsum, ycount, accumulate, status);
     return launch_status();
 }

@@ -49,8 +49,10 @@ def test_workspace_sizes(B):
     assert B.aweq_workspace_size(B.OP_CALIB_STATS, 8, 8) == 8 * 16
     assert B.aweq_workspace_size(B.OP_CALIB_STATS, 0, 8) == 0
     assert B.aweq_workspace_size(B.OP_QUANT_WEIGHT, 4096, 4096) >= 8
-    for op in (B.OP_EQUALIZE, B.OP_W8A8_GEMM, B.OP_BIAS_CORRECT):
+    for op in (B.OP_EQUALIZE, B.OP_BIAS_CORRECT):
         assert B.aweq_workspace_size(op, 4096, 4096, 4096) == 0
+    # the fused GEMM's output statistics: a key pair and a 64-bit sum per output channel
+    assert B.aweq_workspace_size(B.OP_W8A8_GEMM, 4096, 4096, 11008) == 11008 * 16
 
 
 P = 0x10000  # a fake, 16-byte aligned, never dereferenced "device pointer"
@@ -215,3 +217,24 @@ def test_fold_quant_weight_argument_errors(B):
     assert _code(call, bits=4) == "AWEQ_ERR_BITS"            # row sums are an int8 notion
     assert _code(call, K=24584, ldw=24584) == "AWEQ_ERR_SHAPE"
     assert _code(call, W=P + 8) == "AWEQ_ERR_ALIGN"
+
+
+def test_fused_gemm_argument_errors(B):
+    P = 0x10000
+    ok = dict(xq=P, T=64, K=64, wq=P, N=64, act_step=P, act_zero=P, step_w=P, zero_w=P, rowsum_x=P, rowsum_w=P, bias=None,
+              act=0, out_f16=P, ldo=64, colsum_acc=P, ycmin=P, ycmax=P, ycsum=P, ycount=P, accumulate=0, next_inv_s=P,
+              next_step=P, next_zero=P, yq=P, rowsum_y=P, colsum_yq=P, ws=P, ws_bytes=64 * 16, stream=0)
+    assert B.aweq_workspace_size(B.OP_W8A8_GEMM, 64, 64, 64) == 64 * 16
+    call = lambda **kw: B.aweq_w8a8_gemm_fused(**{**ok, **kw})
+    assert _code(call, colsum_acc=None) == "AWEQ_ERR_NULL"
+    assert _code(call, ycmin=None, yq=None) == "AWEQ_ERR_NULL"      # at least one fused epilogue
+    assert _code(call, ycmax=None) == "AWEQ_ERR_NULL"
+    assert _code(call, next_step=None) == "AWEQ_ERR_NULL"
+    assert _code(call, act=2) == "AWEQ_ERR_SHAPE"
+    assert _code(call, N=62, ldo=62) == "AWEQ_ERR_SHAPE"            # the tiled kernel stores channel quads
+    assert _code(call, ldo=32) == "AWEQ_ERR_SHAPE"
+    assert _code(call, K=65536) == "AWEQ_ERR_SHAPE"
+    assert _code(call, ws_bytes=100) == "AWEQ_ERR_WORKSPACE"
+    assert _code(call, ws=None, ws_bytes=0) == "AWEQ_ERR_WORKSPACE"
+    assert _code(call, next_inv_s=P + 4) == "AWEQ_ERR_ALIGN"
+    assert _code(call, bias=P + 4) == "AWEQ_ERR_ALIGN"
