@@ -200,3 +200,56 @@ def test_fused_output_feeds_the_next_layers_calibration(B, orc):
     assert torch.equal(cmin, f["cmin"]) and torch.equal(cmax, f["cmax"])
     mean_abs = np.abs(y.astype(np.float64)).mean(axis=0)
     assert np.all(np.abs(host(csum) - host(f["csum"])) / T <= 1e-6 * mean_abs + 1e-12)
+
+
+def test_fused_fullsize(B, orc):
+    """T = 262144 tokens, 4096 x 4096 (the launch configuration of the benchmark's attention linears):
+    statistics and codes of the whole output against the oracle's passes over the stored output."""
+    T, K, N = 262144, 4096, 4096
+    progress(f"full size T={T} K={K} N={N}")
+    g = torch.Generator(device=DEV)
+    g.manual_seed(5)
+    xq_rm = torch.clamp(torch.round(torch.randn((T, K), generator=g, device=DEV) * 3.0), -128, 127).to(torch.int8)
+    xq_rm[:, 7] = torch.randint(-128, 128, (T,), generator=g, device=DEV, dtype=torch.int32).to(torch.int8)
+    wq_rm = torch.clamp(torch.round(torch.randn((N, K), generator=g, device=DEV) * 40.0), -128, 127).to(torch.int8)
+    xq, wq = e(B.aweq_panel_bytes(T, K), dtype=torch.int8), e(B.aweq_panel_bytes(N, K), dtype=torch.int8)
+    B.aweq_pack_panels_i8(xq_rm, T, K, K, xq)
+    B.aweq_pack_panels_i8(wq_rm, N, K, K, wq)
+
+    class D:
+        pass
+    d = D()
+    d.xq, d.wq = xq, wq
+    d.rowsum_x = xq_rm.sum(dim=1, dtype=torch.int32)
+    d.rowsum_w = wq_rm.sum(dim=1, dtype=torch.int32)
+    rng = np.random.default_rng(6)
+    c = dict(T=T, K=K, N=N)
+    d.step_x, d.zero_x = dev(np.array([0.021], np.float32)), dev(np.array([131], np.int32))
+    d.step_w, d.zero_w = dev(rng.uniform(5e-4, 2e-3, N).astype(np.float32)), dev(rng.integers(100, 156, N).astype(np.int32))
+    d.bias = dev((rng.standard_normal(N) * 0.5).astype(np.float32))
+    del xq_rm, wq_rm
+    y_ref, cs_ref = unfused(B, c, d)
+    assert np.isfinite(y_ref.astype(np.float32)).all()
+    y_ref = np.maximum(y_ref, np.float16(0))
+    inv_s = rng.uniform(0.2, 3.0, N).astype(np.float32)
+    hi = np.float32((y_ref[::16].astype(np.float32) * inv_s[None, :]).max())
+    step, zero, _ = orc.qparams(np.float32(0.0), hi, 8)
+    nxt = dict(inv_s=inv_s, step=step, zero=zero)
+    progress("fused launch")
+    f = fused(B, c, d, act=1, store=True, stats=True, nxt=nxt)
+    assert np.array_equal(host(f["y"]).astype(np.float32), y_ref.astype(np.float32))
+    assert np.array_equal(host(f["colsum_acc"]), cs_ref)
+    progress("oracle statistics over the stored output (host)")
+    st = orc.col_stats(y_ref)
+    assert np.array_equal(host(f["cmin"]), st["cmin"]) and np.array_equal(host(f["cmax"]), st["cmax"])
+    # the epilogue's sums are exact; the oracle's fp64 running sums round: |error| <= T 2^-53 sum|y|
+    abs_sum = np.abs(y_ref[::8].astype(np.float64)).sum(axis=0) * 8.5
+    assert np.all(np.abs(host(f["csum"]) - st["csum"]) <= T * 2.0 ** -53 * abs_sum + 1e-9)
+    progress("oracle activation quantizer over the stored output (host)")
+    a = orc.quant_act(y_ref, nxt["inv_s"], nxt["step"], nxt["zero"])
+    assert np.array_equal(host(f["rowsum_y"]), a["rowsum_x"]) and np.array_equal(host(f["colsum_yq"]), a["colsum_xq"])
+    rows = np.unique(np.concatenate([np.arange(300), np.arange(T - 300, T), rng.integers(0, T, 300)])).astype(np.int64)
+    idx = torch.from_numpy(rows).to(DEV)
+    got = f["yq"].view(N // 64, T, 64)[:, idx, :].permute(1, 0, 2).reshape(-1, N)
+    assert np.array_equal(host(got), a["xq"][rows])
+    assert int(host(f["status"])[0]) == a["status"]
