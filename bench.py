@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--library-gemm", action="store_true",
                     help="context, not the product: time the ROCm library's int8 GEMM (torch._int_mm) and fp16 GEMM on "
                          "the operands one calibrated layer produces, next to aweq_w8a8_gemm / aweq_wonly_gemm")
+    ap.add_argument("--fused-chain", action="store_true",
+                    help="OPT-6.7B fc1 -> ReLU -> fc2: the statistics pass and the activation quantizer of fc2's input as "
+                         "passes of their own over fc1's output, against aweq_w8a8_gemm_fused doing them in fc1's epilogue")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="only run a plain device copy of this many bytes (reference for the HBM counters) and exit")
     return ap.parse_args()
@@ -354,6 +357,92 @@ def library_gemm(args, torch, B, pipeline, synth, dev):
     return {"library_gemm": out, "workload": f"cfg{wl.cfg} {wl.name}"}
 
 
+def fused_chain(args, torch, B, pipeline, synth, dev):
+    """fc1 -> ReLU -> fc2 of the OPT-6.7B-shaped block: what the fused epilogues save.
+    Calibration flow: fc2's statistics come out of fc1's GEMM (its output is still stored and
+    quantised by a pass of its own once fc2's scales exist).  Deployed flow (static scales
+    known): fc1's GEMM writes fc2's int8 codes directly and no binary16 output at all."""
+    wl = synth.WORKLOADS[2]
+    T = args.tokens or wl.T
+    fc1, fc2 = wl.linears[4], wl.linears[5]
+    seed = synth.layer_seed(wl.cfg, 4)
+    X = synth.make_act_torch(seed, T, fc1.K, wl, dev)
+    W1 = synth.make_weight_torch(seed, fc1.N, fc1.K, wl.dtype, dev)
+    b1 = torch.from_numpy(synth.make_bias_np(seed, fc1.N, True)).to(dev)
+    W2 = synth.make_weight_torch(synth.layer_seed(wl.cfg, 5), fc2.N, fc2.K, wl.dtype, dev)
+    buf = pipeline.LayerBuffers(T, fc1.K, fc1.N, torch.float16, want_out_i32=False, want_out_deq=True, device=dev)
+    t = pipeline.calibrate_layer(X, W1, b1, buf, fused_weight_pass=True)
+    torch.cuda.synchronize()
+    del X
+    K, N = fc1.K, fc1.N
+    y = t["out_deq"]
+    y.clamp_(min=0)                       # ReLU: fc2's input for the separate passes
+    b2 = pipeline.LayerBuffers(T, fc2.K, fc2.N, torch.float16, want_out_i32=False, device=dev)
+    u = b2.t
+    f32, i32, i64 = torch.float32, torch.int32, torch.int64
+    e = lambda *shape, dtype: torch.empty(shape, dtype=dtype, device=dev)
+    ws = e(B.aweq_workspace_size(B.OP_W8A8_GEMM, T, K, N), dtype=torch.uint8)
+    fmin, fmax, fsum, fcnt = e(N, dtype=f32), e(N, dtype=f32), e(N, dtype=torch.float64), torch.zeros(1, dtype=i64, device=dev)
+    yq, rsy, csy = e(B.aweq_panel_bytes(T, N), dtype=torch.int8), e(T, dtype=i32), e(N, dtype=i64)
+
+    def gemm_plain():
+        B.aweq_w8a8_gemm(t["xq"], B.AWEQ_I8, T, K, K, None, t["act_step"], t["act_zero"], None, t["rowsum_x"], None, t["codes"],
+                         N, t["step_w"], t["zero_w"], t["rowsum_w"], b1, None, y, B.AWEQ_F16, N, t["colsum_acc"], None)
+
+    def stats_y():
+        B.aweq_calib_stats(y, B.AWEQ_F16, T, N, N, u["xmin"], u["xmax"], u["xsum"], u["count"], 0, 1, u["r_x"], u["R_x"],
+                           u["p_x"], u["ws"])
+
+    def quant_y():
+        B.aweq_quant_act(y, B.AWEQ_F16, T, N, N, u["inv_s"], u["act_step"], u["act_zero"], u["xq"], u["rowsum_x"], u["colsum_xq"])
+
+    def fused(store, stats, quant):
+        B.aweq_w8a8_gemm_fused(t["xq"], T, K, t["codes"], N, t["act_step"], t["act_zero"], t["step_w"], t["zero_w"],
+                               t["rowsum_x"], t["rowsum_w"], b1, 1, y if store else None, N, t["colsum_acc"],
+                               fmin if stats else None, fmax if stats else None, fsum if stats else None,
+                               fcnt if stats else None, 0, u["inv_s"] if quant else None, u["act_step"] if quant else None,
+                               u["act_zero"] if quant else None, yq if quant else None, rsy if quant else None,
+                               csy if quant else None, ws)
+
+    # fc2's scales from the separate statistics pass (the fused statistics must agree: checked below)
+    stats_y()
+    B.aweq_calib_stats(W2, B.AWEQ_F16, fc2.N, fc2.K, fc2.K, u["wmin"], u["wmax"], None, u["wcount"], 0, 1, u["r_w"], u["R_w"],
+                       u["p_w"], u["ws"])
+    B.aweq_equalize(u["xmin"], u["xmax"], u["xsum"], T, u["wmin"], u["wmax"], fc2.K, 1, u["s"], u["inv_s"], None, u["W_hat"],
+                    B.AWEQ_F16, fc2.N, fc2.K, None, u["xhat_range"], u["mu_xhat"], u["act_step"], u["act_zero"])
+    quant_y()
+    fused(True, True, True)
+    torch.cuda.synchronize()
+    same = bool(torch.equal(fmin, u["xmin"]) and torch.equal(fmax, u["xmax"]) and torch.equal(yq, u["xq"])
+                and torch.equal(rsy, u["rowsum_x"]) and torch.equal(csy, u["colsum_xq"]))
+
+    def timed(fn, n=6, w=3):
+        for _ in range(w):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in ev)
+        return ts[len(ts) // 2]
+
+    ms = {"gemm_fp16_out": timed(gemm_plain), "stats_pass_over_y": timed(stats_y), "quant_act_pass_over_y": timed(quant_y),
+          "gemm_fused_statistics_fp16_out": timed(lambda: fused(True, True, False)),
+          "gemm_fused_codes_no_fp16_out": timed(lambda: fused(False, False, True)),
+          "gemm_fused_statistics_and_codes_fp16_out": timed(lambda: fused(True, True, True))}
+    ops = 2.0 * T * N * K
+    return {"fused_chain": {"layers": "cfg2 fc1 (16384 x 4096) -> ReLU -> fc2 input", "T": T, "ms": {k: round(v, 4) for k, v in ms.items()},
+                            "calibration_flow_ms": {"separate": round(ms["gemm_fp16_out"] + ms["stats_pass_over_y"], 4),
+                                                    "fused": round(ms["gemm_fused_statistics_fp16_out"], 4)},
+                            "deployed_flow_ms": {"separate": round(ms["gemm_fp16_out"] + ms["quant_act_pass_over_y"], 4),
+                                                 "fused": round(ms["gemm_fused_codes_no_fp16_out"], 4)},
+                            "gemm_TOPs": {k: round(ops / v / 1e9, 1) for k, v in ms.items() if k.startswith("gemm")},
+                            "fused_results_identical_to_separate_passes": same}}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -375,6 +464,9 @@ def main():
         return
     if args.library_gemm:
         print(json.dumps(library_gemm(args, torch, B, pipeline, synth, dev)))
+        return
+    if args.fused_chain:
+        print(json.dumps(fused_chain(args, torch, B, pipeline, synth, dev)))
         return
     if args.copy_probe:
         # a plain copy kernel of known size: what FETCH_SIZE / WRITE_SIZE read for it gives the

@@ -145,6 +145,36 @@ __device__ __forceinline__ int quant_div(float x, float step, int zero, int qmax
     return min(max(u, 0), qmax);
 }
 
+// Constants of the static int8 activation quantizer (Eq. 1 with b = 8) for the division-free
+// paths: `fast` = the exact two-correction quotient is valid for binary16 inputs, `screen` = the
+// one-FMA quotient with its distance-to-tie test is (both are explained where they are used, in
+// the activation quantizer).
+struct ActParams {
+    float step, rstep, lo_f, hi_f, thr;
+    int zero, zoff;
+    bool fast, screen;
+};
+
+__device__ __forceinline__ ActParams act_params(const float* act_step, const int32_t* act_zero, bool f16)
+{
+    ActParams p;
+    p.step = *act_step;
+    p.zero = *act_zero;
+    p.rstep = 1.0f / p.step;
+    const uint32_t b = __float_as_uint(p.step);
+    const int e = (int)((b >> 23) & 0xff) - 127;
+    const uint32_t m = b & 0x7fffffu;
+    p.fast = f16 && (b >> 31) == 0 && e >= -60 && e <= 60 && m < 0x7ffff0u && p.zero > -(1 << 23) && p.zero < (1 << 23);
+    // screened quotient: |Z| small enough for delta to stay far below 1/2
+    const int az = p.zero < 0 ? -p.zero : p.zero;
+    p.screen = p.fast && az <= 4096;
+    p.thr = 0.5f - ((float)(258 + (az <= 4096 ? az : 0)) * 1.1920928955078125e-07f + 3.0517578125e-05f);
+    p.lo_f = (float)(-p.zero);
+    p.hi_f = (float)(255 - p.zero);
+    p.zoff = p.zero - 128;
+    return p;
+}
+
 __device__ __forceinline__ void raise_status(uint32_t* status, uint32_t st)
 {
     if (status && st) atomicOr(status, st);

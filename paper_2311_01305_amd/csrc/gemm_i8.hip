@@ -399,9 +399,9 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
     // three panels, so "at most kStores operations pending" means those panels have landed
     // while the stores may still be on their way (relaxed: set for the tile that follows).
     static_assert(EPI == 0 || DEQ == 2, "the fused epilogues work on the binary16 output");
-    // 4 sub-tile rows x 8 passes each; the fused variants never take the relaxed wait (their
-    // atomics are not counted here)
-    constexpr int kStoresAll = EPI != 0 ? 0 : ((I32 ? 32 : 0) + (DEQ != 0 && STORE ? 32 : 0));
+    // 4 sub-tile rows x 8 passes each, per kind of output; the atomics of the fused epilogues come
+    // on top and are not counted: a lower bound is what the relaxed wait needs
+    constexpr int kStoresAll = (I32 ? 32 : 0) + (DEQ != 0 && STORE ? 32 : 0) + ((EPI & 2) != 0 ? 32 : 0);
     constexpr int kStores = kStoresAll > 63 ? 63 : kStoresAll;
     bool relaxed = false;
 
@@ -543,15 +543,24 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
             sxf = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sxf)));
         }
         Float4 nis = {{1.f, 1.f, 1.f, 1.f}};   // the next layer's 1 / s for this lane's four channels
-        float nstep = 1.0f;
+        float nstep = 1.0f, nrstep = 1.0f, nthr = 0.0f;
         int nzero = 0;
+        bool nscreen = false;
         if constexpr ((EPI & 2) != 0) {
             if (n_ok) nis = *reinterpret_cast<const Float4*>(g.next_inv_s + n);
-            nstep = *g.next_step;
-            nzero = *g.next_zero;
+            const ActParams np_ = act_params(g.next_step, g.next_zero, true);
+            nstep = np_.step; nzero = np_.zero; nrstep = np_.rstep; nthr = np_.thr;
+            // the one-FMA quotient with its distance-to-tie test (see the activation quantizer): valid
+            // for this lane if no binary16 value times its 1 / s can reach a quotient of 2^24
+            nscreen = np_.screen;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(nis.f[c]));
+            for (int c = 0; c < 4; ++c) {
+                asm volatile("" : "+v"(nis.f[c]));
+                nscreen = nscreen && 65600.0f * fabsf(nis.f[c]) * nrstep < 16777216.0f;
+            }
             nstep = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(nstep)));
+            nrstep = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(nrstep)));
+            nthr = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(nthr)));
             nzero = __builtin_amdgcn_readfirstlane(nzero);
         }
 
@@ -582,7 +591,8 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         long long csum[4] = {0, 0, 0, 0};
         float ymn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, ymx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         double ysum[4] = {0.0, 0.0, 0.0, 0.0};   // exact: at most 128 binary16 values each
-        int cq[4] = {0, 0, 0, 0};                // column sums of the next layer's codes over this tile
+        float cqf[4] = {0.f, 0.f, 0.f, 0.f};     // column sums of the next layer's unsigned codes over this tile (exact: 32 rows)
+        int cq_rows = 0;
         uint32_t est = 0;
         const bool yq_pad = (EPI & 2) != 0 && !n_ok && cn0 + wn * 64 < g.N;   // zero fill of the last panel
         int8_t* const yq_lane = (EPI & 2) != 0 ? g.yq + (((cn0 >> 6) + wn) * g.T) * kPanel + rd_c * 4 : nullptr;
@@ -636,13 +646,30 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                             }
                             if constexpr ((EPI & 2) != 0) {
                                 uint32_t w = 0;
+                                const float zf = (float)nzero;
+                                float cn_[4];
+                                float dmax = 0.0f;
 #pragma unroll
                                 for (int c = 0; c < 4; ++c) {
-                                    const int code = quant_div((float)oh[c] * nis.f[c], nstep, nzero, 255, est) - 128;
-                                    cq[c] += code;
-                                    rsy += code;
-                                    w |= (uint32_t)(code & 0xff) << (8 * c);
+                                    const float a = __builtin_fmaf((float)oh[c], nis.f[c], 0.0f);
+                                    const float q = __builtin_fmaf(a, nrstep, zf);
+                                    cn_[c] = rintf(q);
+                                    dmax = fmaxf(dmax, fabsf(q - cn_[c]));
                                 }
+                                if (!nscreen || dmax > nthr) {
+#pragma unroll
+                                    for (int c = 0; c < 4; ++c)
+                                        cn_[c] = (float)quant_div((float)oh[c] * nis.f[c], nstep, nzero, 255, est);
+                                }
+#pragma unroll
+                                for (int c = 0; c < 4; ++c) {
+                                    const float u = __builtin_amdgcn_fmed3f(cn_[c], 0.0f, 255.0f);
+                                    cqf[c] += u;
+                                    w = __builtin_amdgcn_cvt_pk_u8_f32(u, c, w);
+                                }
+                                w ^= 0x80808080u;   // u - 128 as a byte
+                                rsy = __builtin_amdgcn_sdot4((int)w, 0x01010101, 0, false);
+                                ++cq_rows;
                                 *reinterpret_cast<uint32_t*>(yq_lane + t * kPanel) = w;
                             }
                         } else {
@@ -688,8 +715,10 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
             }
         }
         if constexpr ((EPI & 2) != 0) {
+            int cq[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
+                cq[c] = (int)cqf[c] - 128 * cq_rows;
                 cq[c] += partner<4>(cq[c]);
                 cq[c] += partner<5>(cq[c]);
             }
