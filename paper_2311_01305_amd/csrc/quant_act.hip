@@ -108,7 +108,8 @@ __device__ __forceinline__ void act_unit(const float x[8], const float is[8], co
     }
     rs = __builtin_amdgcn_sdot4((int)w[0], 0x01010101, rs, false);
     rs = __builtin_amdgcn_sdot4((int)w[1], 0x01010101, rs, false);
-    *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+    typedef unsigned v2u_ __attribute__((ext_vector_type(2)));
+    __builtin_nontemporal_store(v2u_{w[0], w[1]}, reinterpret_cast<v2u_*>(dst));
 }
 
 // 8 consecutive input values of one row as loaded (binary16: one 16-byte quad), converted to
@@ -116,7 +117,12 @@ __device__ __forceinline__ void act_unit(const float x[8], const float is[8], co
 template <bool F16> struct RawUnit;
 template <> struct RawUnit<true> {
     Half8 v;
-    __device__ __forceinline__ void load(const void* X, int64_t elt) { v = *reinterpret_cast<const Half8*>(reinterpret_cast<const _Float16*>(X) + elt); }
+    __device__ __forceinline__ void load(const void* X, int64_t elt)
+    {
+        typedef int v4i_ __attribute__((ext_vector_type(4)));
+        const v4i_ r = __builtin_nontemporal_load(reinterpret_cast<const v4i_*>(reinterpret_cast<const _Float16*>(X) + elt));
+        v = __builtin_bit_cast(Half8, r);
+    }
     __device__ __forceinline__ void get(float x[8]) const
     {
 #pragma unroll
