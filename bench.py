@@ -55,6 +55,9 @@ def parse():
     ap.add_argument("--fused-chain", action="store_true",
                     help="OPT-6.7B fc1 -> ReLU -> fc2: the statistics pass and the activation quantizer of fc2's input as "
                          "passes of their own over fc1's output, against aweq_w8a8_gemm_fused doing them in fc1's epilogue")
+    ap.add_argument("--ablation", action="store_true",
+                    help="context: output error of the quantised layer on the synthetic workload for the AWE x BC grid "
+                         "(W8A8, and W4 / W3 weight-only), first linear of --cfg at 32768 tokens")
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="only run a plain device copy of this many bytes (reference for the HBM counters) and exit")
     return ap.parse_args()
@@ -443,6 +446,52 @@ def fused_chain(args, torch, B, pipeline, synth, dev):
                             "fused_results_identical_to_separate_passes": same}}
 
 
+def ablation(args, torch, B, pipeline, synth, dev):
+    """The switches of the paper's ablation (equalization on / off, bias correction on / off) on one
+    synthetic layer: relative RMS error and mean error of the quantised layer's output against the
+    fp64 product of the un-quantised layer.  Context only: synthetic tensors, not the paper's tasks."""
+    wl = synth.WORKLOADS[args.cfg]
+    T = args.tokens or 32768
+    lin = wl.linears[0]
+    seed = synth.layer_seed(wl.cfg, 0)
+    X = synth.make_act_torch(seed, T, lin.K, wl, dev)
+    W = synth.make_weight_torch(seed, lin.N, lin.K, wl.dtype, dev)
+    b_np = synth.make_bias_np(seed, lin.N, wl.has_bias)
+    b = None if b_np is None else torch.from_numpy(b_np).to(dev)
+    K, N = lin.K, lin.N
+    y = X.to(torch.float64) @ W.to(torch.float64).t()        # the reference the error is measured against
+    if b is not None:
+        y += b.to(torch.float64)
+    rms_y = float(y.pow(2).mean().sqrt())
+    rows = []
+    for mode, bits in (("w8a8", 8), ("w4 g128, fp16 activations", 4), ("w3 g128, fp16 activations", 3)):
+        for awe in (0, 1):
+            for bc in (0, 1):
+                if bits == 8:
+                    buf = pipeline.LayerBuffers(T, K, N, torch.float16, want_out_i32=False, want_out_deq=True, device=dev)
+                    t = pipeline.calibrate_layer(X, W, b, buf, enable_awe=bool(awe), enable_bc=bool(bc))
+                    yq = t["out_deq"].to(torch.float64)
+                    if b is not None:
+                        yq -= b.to(torch.float64)
+                    yq += t["bias_out"].to(torch.float64)
+                else:
+                    buf = pipeline.LayerBuffers(T, K, N, torch.float16, bits=bits, group=128, w8a8=False, device=dev)
+                    t = pipeline.calibrate_layer(X, W, b, buf, enable_awe=bool(awe), enable_bc=bool(bc))
+                    # the deployed layer sees the equalised activation: X diag(s)^-1 in binary16
+                    Xh = (X.to(torch.float32) * t["inv_s"]).to(torch.float16)
+                    yh = torch.empty((T, N), dtype=torch.float32, device=dev)
+                    ws = torch.empty(B.aweq_workspace_size(B.OP_WONLY_GEMM, T, K, N), dtype=torch.uint8, device=dev)
+                    B.aweq_wonly_gemm(Xh, T, K, K, t["codes"], bits, 128, t["step_w"], t["zero_w"], N, t["bias_out"], yh,
+                                      B.AWEQ_F32, N, ws)
+                    yq = yh.to(torch.float64)
+                e = yq - y
+                rows.append({"mode": mode, "awe": awe, "bc": bc, "rel_rms_error": float(e.pow(2).mean().sqrt()) / rms_y,
+                             "max_abs_channel_mean_error": float(e.mean(dim=0).abs().max()),
+                             "status_bits": int(t["status"].item())})
+                del buf, t, yq, e
+    return {"ablation": rows, "layer": f"cfg{wl.cfg} {lin.name} {N}x{K}", "T": T, "rms_of_reference_output": rms_y}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -464,6 +513,9 @@ def main():
         return
     if args.library_gemm:
         print(json.dumps(library_gemm(args, torch, B, pipeline, synth, dev)))
+        return
+    if args.ablation:
+        print(json.dumps(ablation(args, torch, B, pipeline, synth, dev)))
         return
     if args.fused_chain:
         print(json.dumps(fused_chain(args, torch, B, pipeline, synth, dev)))
