@@ -643,6 +643,19 @@ def main():
             "gemm_TOPs": round(2.0 * T * lin.N * lin.K / (ms["gemm"] * 1e-3) / 1e12, 1),
         })
 
+    # the two streaming passes over X against the HBM peak (event-timed calls, all layers of the step)
+    sx_bytes = sum(T * lin.K * esz for lin, *_ in layers)
+    qa_bytes = sum(T * lin.K * (esz + 1) for lin, *_ in layers)
+    sx_ms = sum(pl["ms"]["stats_x"] for pl in per_layer)
+    qa_ms = sum(pl["ms"]["quant_act"] for pl in per_layer)
+    hbm_passes = [
+        {"bound": "hbm", "kernel": "col_stats_partial_f16 + merge + finalize (the aweq_calib_stats call on X)",
+         "achieved": sx_bytes / (sx_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": sx_bytes / (sx_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "bytes_per_element": esz},
+        {"bound": "hbm", "kernel": "quant_act_kernel (+ two fill kernels: the aweq_quant_act call)",
+         "achieved": qa_bytes / (qa_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": qa_bytes / (qa_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "bytes_per_element": esz + 1}]
+
     traffic = None
     if T == 262144 and all((lin.N, lin.K) in GEMM_TRAFFIC_BYTES for lin, *_ in layers):
         traffic = sum(sum(GEMM_TRAFFIC_BYTES[(lin.N, lin.K)]) for lin, *_ in layers) / len(layers) / 1e9
@@ -677,6 +690,7 @@ def main():
                                      f"algorithmic {algorithmic_gb:.1f} GB: operands once + int32 output)",
                      "note": "int8 multiply-add = 2 ops (TOP/s); achieved = sum 2*T*N*K / sum of event-timed GEMM "
                              f"launches ({n_gemm} launches, avg {gemm_ms_total / n_gemm:.3f} ms)"},
+        "roofline_hbm_passes": hbm_passes,
         "layers": per_layer,
         "status_bits": status_bits,
     }
