@@ -776,13 +776,16 @@ using namespace aweq;
 namespace aweq {
 
 // tile / patch plan of a launch
-static int plan_gemm(GemmArgs& g, int64_t T, int64_t N, int64_t& blocks)
+static int plan_gemm(GemmArgs& g, int64_t T, int64_t N, int64_t K, int64_t& blocks)
 {
     const int64_t tiles_m = cdiv(T, BM), tiles_n = cdiv(N, BN);
     if (tiles_m * tiles_n > (1ll << 30)) return AWEQ_ERR_SHAPE;
     g.tiles_m = (int)tiles_m; g.tiles_n = (int)tiles_n;
-    // patch of output tiles an XCD works on at a time: 32 tiles (one per compute unit)
-    g.patch_n = (int)(tiles_n < 4 ? tiles_n : 4);
+    // patch of output tiles an XCD works on at a time: 32 tiles (one per compute unit), 8 (t) x 4 (n);
+    // 4 x 8 when the contraction is long against N: the activation panels, the operand that does not
+    // fit the memory-side cache, are then fetched half as often (1-2 % here, 9 % in the binary16 GEMM)
+    const int want_n = K >= 2 * N ? 8 : 4;
+    g.patch_n = (int)(tiles_n < want_n ? tiles_n : want_n);
     g.patch_m = 32 / g.patch_n;
     if (g.patch_m > tiles_m) g.patch_m = (int)tiles_m;
     g.patches_n = (int)cdiv(tiles_n, g.patch_n);
@@ -898,7 +901,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     g.rowsum_x = rowsum_x; g.rowsum_w = rowsum_w; g.bias = bias;
     clear_fused(g);
     int64_t blocks = 0;
-    const int prc = plan_gemm(g, T, N, blocks);
+    const int prc = plan_gemm(g, T, N, K, blocks);
     if (prc != AWEQ_OK) return prc;
 
     if (colsum_acc) zero_fill_u32_gemm<<<(unsigned)cdiv(2 * N, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_acc), 2 * N);
@@ -968,7 +971,7 @@ extern "C" int aweq_w8a8_gemm_fused(const int8_t* xq, int64_t T, int64_t K, cons
         g.yq = yq; g.rowsum_y = rowsum_y; g.colsum_yq = reinterpret_cast<long long*>(colsum_yq);
     }
     int64_t blocks = 0;
-    const int prc = plan_gemm(g, T, N, blocks);
+    const int prc = plan_gemm(g, T, N, K, blocks);
     if (prc != AWEQ_OK) return prc;
 
     hipStream_t st = as_stream(stream);

@@ -402,8 +402,12 @@ extern "C" int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t 
     g.W = W; g.bias = bias;
     g.out = out; g.ldo = ldo; g.T = T; g.N = N; g.K = K;
     g.tiles_m = (int)tiles_m; g.tiles_n = (int)tiles_n;
-    // patch of output tiles an XCD works on at a time: 32 tiles (one per compute unit)
-    g.patch_n = (int)(tiles_n < 4 ? tiles_n : 4);
+    // patch of output tiles an XCD works on at a time: 32 tiles (one per compute unit), 8 (t) x 4 (n);
+    // 4 x 8 when the contraction is long against N: the strided binary16 activation rows are then
+    // fetched half as often and the weight, which fits the memory-side cache, twice as often
+    // (1227 -> 1342 TFLOP/s at 4096 x 11008, 1236 -> 1342 at 4096 x 16384; 4096 x 4096 and 11008 x 4096 prefer 8 x 4)
+    const int want_n = K >= 2 * N ? 8 : 4;
+    g.patch_n = (int)(tiles_n < want_n ? tiles_n : want_n);
     g.patch_m = 32 / g.patch_n;
     if (g.patch_m > tiles_m) g.patch_m = (int)tiles_m;
     g.patches_n = (int)cdiv(tiles_n, g.patch_n);

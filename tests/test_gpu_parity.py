@@ -493,6 +493,7 @@ def gpu_gemm(B, xq, wq, want_i32=True, deq=None, colsum=True):
     (5157, 4100, 512),   # 21 x 17 = 357 tiles on 256 persistent workgroups: second tiles, ragged edges on
                          # both sides, the relaxed wait after interior tiles and the full wait after edge tiles
     (5157, 4100, 320),   # the same with five panels (never relaxed)
+    (700, 2304, 4608),   # K >= 2 N with nine tile columns: the 4 x 8 patch shape, ragged on both sides
 ])
 def test_gemm_parity(B, orc, T, N, K):
     progress(f"gemm T={T} N={N} K={K}")

@@ -82,6 +82,7 @@ def test_zero_point_outside_the_packed_path(B, orc):
     (4, 256, 256, 64, 0), (3, 1, 4, 64, -1),
     (4, 700, 2100, 128, 128),        # more than one patch along N
     (4, 1000, 512, 4096, 128), (3, 777, 300, 4096, 128),   # the K of the LLaMA-7B attention linears
+    (4, 300, 2052, 4224, 128),       # K >= 2 N with nine tile columns: the 4 x 8 patch shape
 ])
 def test_forward_parity(B, orc, odt, bits, T, N, K, group):
     progress(f"forward W{bits} {odt.__name__} T={T} N={N} K={K} g={group}")
