@@ -589,6 +589,10 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         const int wr_t = lane & 31;
         const int wr_sw = wr_t & 15, wr_half = lane >> 5;           // chunk (8 j + 2 q + l / 32) ^ (t & 15)
         long long csum[4] = {0, 0, 0, 0};
+        // with a de-quantised output the column sums come from the corrected integers that are converted
+        // anyway (exact in fp64: 32 values below 2^31): sum acc = sum iv - rows cn + Z'w sum rowsum_x
+        double dsum[4] = {0.0, 0.0, 0.0, 0.0};
+        int rs_sum = 0, rows_in = 0;
         float ymn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, ymx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         double ysum[4] = {0.0, 0.0, 0.0, 0.0};   // exact: at most 128 binary16 values each
         float cqf[4] = {0.f, 0.f, 0.f, 0.f};     // column sums of the next layer's unsigned codes over this tile (exact: 32 rows)
@@ -621,9 +625,16 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                         float y[4];
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
-                            const unsigned iv = (unsigned)o[c] + cn[c] - zw[c] * rs;
-                            y[c] = (float)((double)(int)iv * scale[c] + bsd[c]);
+                            // |Z'w| <= 128 and |row sum| <= 128 K < 2^23: a 24-bit multiply-add (full rate)
+                            const int iv = (int)((unsigned)o[c] + cn[c]) - __mul24((int)zw[c], (int)rs);
+                            const double div = (double)iv;
+                            // the binary32 output is the fp64 product and sum rounded once (two fp64 operations,
+                            // like the definition); for binary16 one fused fp64 operation is far inside the rounding
+                            if constexpr (DEQ == 1) y[c] = (float)(div * scale[c] + bsd[c]);
+                            else y[c] = (float)__builtin_fma(div, scale[c], bsd[c]);
+                            if constexpr (COLSUM) dsum[c] += div;
                         }
+                        if constexpr (COLSUM) { rs_sum += (int)rs; ++rows_in; }
                         if constexpr (DEQ == 2) {
                             typedef _Float16 h4 __attribute__((ext_vector_type(4)));
                             if constexpr (EPI != 0) {
@@ -678,7 +689,7 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                             __builtin_nontemporal_store(of, reinterpret_cast<f4*>(reinterpret_cast<float*>(g.out_deq) + t * g.ldo + n));
                         }
                     }
-                    if constexpr (COLSUM) {
+                    if constexpr (COLSUM && DEQ == 0) {
 #pragma unroll
                         for (int c = 0; c < 4; ++c) csum[c] += o[c];
                     }
@@ -730,6 +741,11 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         }
         if constexpr (EPI != 0) raise_status(g.status, est);
         if constexpr (COLSUM) {
+            if constexpr (DEQ != 0) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    csum[c] = (long long)dsum[c] - (long long)rows_in * (long long)(int)cn[c] + (long long)(int)zw[c] * (long long)rs_sum;
+            }
             // lanes l, l ^ 16, l ^ 32 hold the same channels for different tokens
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
