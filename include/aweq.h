@@ -50,7 +50,9 @@ enum {
     AWEQ_ST_DEGENERATE = 1u, /* Eq. 2 gave a non-positive or non-finite Step; Step := 1 was used */
     AWEQ_ST_NONFINITE = 2u,  /* NaN / Inf seen in the input (results unspecified) */
     AWEQ_ST_BIGQUOT = 4u,    /* |x / Step| >= 2^24: quotient saturated */
-    AWEQ_ST_SCALEGUARD = 8u  /* Eq. 10: a channel range was < 1e-5 (s := 1) or s was clamped to [1e-4, 1e4] */
+    AWEQ_ST_SCALEGUARD = 8u, /* Eq. 10: a channel range was < 1e-5 (s := 1) or s was clamped to [1e-4, 1e4] */
+    AWEQ_ST_ZEROPOINT = 16u  /* stage 4 de-quantisation met a zero point outside [0, 255] (a slice whose range does not
+                                contain 0): its 32-bit integer part is exact only while it fits in 32 bits */
 };
 
 typedef enum {
@@ -163,6 +165,9 @@ int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t l
  * out_deq[T x N] (F16 or F32, pitch ldo) the de-quantised output
  *   Step_x Step_w[n] (acc - Z'x rowsum_w[n] - Z'w[n] rowsum_x[t] + K Z'x Z'w[n]) + bias[n],
  *   Z' = Z - 128 (needs rowsum_x, rowsum_w, step_w, zero_w; bias nullable);
+ *   The integer in parentheses is formed in 32-bit arithmetic: exact whenever it fits, which zero
+ *   points in [0, 255] (ranges that contain 0) guarantee for K <= 32768; other zero points are
+ *   handled the same way and raise AWEQ_ST_ZEROPOINT;
  * colsum_acc[N] = sum_t acc[t,n] (int64; what stage 5 needs).
  * step_w / zero_w / rowsum_w are indexed by output channel here and in aweq_bias_correct (W8A8
  * mode): for a per-tensor weight quantizer (group = -1) pass the one (Step, Z) repeated N times. */

@@ -15,7 +15,7 @@ _lib = None
 AWEQ_F32, AWEQ_F16, AWEQ_I8 = 0, 1, 2
 OP_CALIB_STATS, OP_EQUALIZE, OP_QUANT_WEIGHT, OP_W8A8_GEMM, OP_BIAS_CORRECT, OP_WONLY_GEMM = 0, 1, 2, 3, 4, 5
 BIAS_W8A8, BIAS_WEIGHT_ONLY = 0, 1
-ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD = 1, 2, 4, 8
+ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD, ST_ZEROPOINT = 1, 2, 4, 8, 16
 
 EXPORTS = ("aweq_workspace_size", "aweq_status_string", "aweq_calib_stats", "aweq_equalize",
            "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock",

@@ -223,6 +223,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_i8_generic(GemmArgs g)
             const int64_t n = col_base + j * 32;
             if (n >= g.N) continue;
             const int zw = g.zero_w[n] - 128;
+            if (zw < -128 || zw > 127 || zx < -128 || zx > 127) raise_status(g.status, AWEQ_ST_ZEROPOINT);
             const double scale = sx * (double)g.step_w[n];
             const double bs = g.bias ? (double)g.bias[n] : 0.0;
             // integer part in wrap-around 32-bit arithmetic: the final value fits (|.| <= 255^2 K)
@@ -510,10 +511,19 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         // so that waiting for it does not wait for them
         int rsx[2] = {0, 0};   // row sums of this wave's 128 tokens, two per lane: token 64 h + lane
         Float4 sw = {{0.f, 0.f, 0.f, 0.f}}, bs = {{0.f, 0.f, 0.f, 0.f}};
-        v4i zr4 = {0, 0, 0, 0};   // (rowsum_w << 8) | (Z'w & 0xff): |rowsum_w| <= 128 K <= 2^22
+        int zwv[4] = {0, 0, 0, 0};          // Z'w = Z_w - 128 of this lane's channels
+        unsigned cn[4] = {0, 0, 0, 0};      // K Z'x Z'w - Z'x rowsum_w, in wrap-around 32-bit arithmetic
+        uint32_t est = 0;                   // status bits this lane raises for the tile
         int zx = 0;
         float sxf = 0.f;
         if constexpr (DEQ != 0) {
+            zx = *g.act_zero - 128;
+            sxf = *g.act_step;
+            zx = __builtin_amdgcn_readfirstlane(zx);
+            sxf = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sxf)));
+            // the integer part is formed in 32-bit arithmetic: exact while it fits, which zero points in
+            // [0, 255] guarantee for K <= 32768; anything else is flagged
+            if (zx < -128 || zx > 127) est |= AWEQ_ST_ZEROPOINT;
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
                 const int64_t t = cm0 + wm * 128 + hh * 64 + lane;
@@ -524,11 +534,13 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                 const v4i zw4 = *reinterpret_cast<const v4i*>(g.zero_w + n);
                 const v4i rw4 = *reinterpret_cast<const v4i*>(g.rowsum_w + n);
 #pragma unroll
-                for (int c = 0; c < 4; ++c) zr4[c] = (int)((unsigned)rw4[c] << 8) | ((zw4[c] - 128) & 0xff);
+                for (int c = 0; c < 4; ++c) {
+                    zwv[c] = zw4[c] - 128;
+                    if (zw4[c] < 0 || zw4[c] > 255) est |= AWEQ_ST_ZEROPOINT;
+                    cn[c] = (unsigned)g.K * (unsigned)zx * (unsigned)zwv[c] - (unsigned)zx * (unsigned)rw4[c];
+                }
                 if (g.bias) bs = *reinterpret_cast<const Float4*>(g.bias + n);
             }
-            zx = *g.act_zero - 128;
-            sxf = *g.act_step;
             // pin the values in registers here: the compiler's wait for them then sits before the
             // panel requests below, which it cannot see, instead of behind them
             asm volatile("" : "+v"(rsx[0]));
@@ -537,10 +549,9 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
             for (int c = 0; c < 4; ++c) {
                 asm volatile("" : "+v"(sw.f[c]));
                 asm volatile("" : "+v"(bs.f[c]));
-                asm volatile("" : "+v"(zr4[c]));
+                asm volatile("" : "+v"(zwv[c]));
+                asm volatile("" : "+v"(cn[c]));
             }
-            zx = __builtin_amdgcn_readfirstlane(zx);
-            sxf = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sxf)));
         }
         Float4 nis = {{1.f, 1.f, 1.f, 1.f}};   // the next layer's 1 / s for this lane's four channels
         float nstep = 1.0f, nrstep = 1.0f, nthr = 0.0f;
@@ -574,15 +585,11 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
 
         // per-channel constants of the de-quantisation
         double scale[4] = {0, 0, 0, 0}, bsd[4] = {0, 0, 0, 0};
-        unsigned cn[4] = {0, 0, 0, 0}, zw[4] = {0, 0, 0, 0};
         if constexpr (DEQ != 0) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                zw[c] = (unsigned)(int)(int8_t)(zr4[c] & 0xff);
                 scale[c] = (double)sxf * (double)sw.f[c];
                 bsd[c] = (double)bs.f[c];
-                // integer part in wrap-around 32-bit arithmetic: the final value fits (|.| <= 255^2 K)
-                cn[c] = (unsigned)g.K * (unsigned)zx * zw[c] - (unsigned)zx * (unsigned)(zr4[c] >> 8);
             }
         }
         char* slab = lds + 3 * kSlot + wave * 8192;
@@ -596,8 +603,6 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         float ymn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, ymx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         double ysum[4] = {0.0, 0.0, 0.0, 0.0};   // exact: at most 128 binary16 values each
         float cqf[4] = {0.f, 0.f, 0.f, 0.f};     // column sums of the next layer's unsigned codes over this tile (exact: 32 rows)
-        int cq_rows = 0;
-        uint32_t est = 0;
         const bool yq_pad = (EPI & 2) != 0 && !n_ok && cn0 + wn * 64 < g.N;   // zero fill of the last panel
         int8_t* const yq_lane = (EPI & 2) != 0 ? g.yq + (((cn0 >> 6) + wn) * g.T) * kPanel + rd_c * 4 : nullptr;
 #pragma unroll
@@ -625,13 +630,17 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                         float y[4];
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
-                            // |Z'w| <= 128 and |row sum| <= 128 K < 2^23: a 24-bit multiply-add (full rate)
-                            const int iv = (int)((unsigned)o[c] + cn[c]) - __mul24((int)zw[c], (int)rs);
+                            // |row sum| <= 128 K < 2^23 and |Z'w| < 2^23 for any zero point binary16 weights can
+                            // produce: a 24-bit multiply (full rate); wider zero points take the 32-bit one
+                            const int zr = (zwv[c] < (1 << 23) && zwv[c] > -(1 << 23)) ? __mul24(zwv[c], (int)rs) : zwv[c] * (int)rs;
+                            const int iv = (int)((unsigned)o[c] + cn[c] - (unsigned)zr);
                             const double div = (double)iv;
                             // the binary32 output is the fp64 product and sum rounded once (two fp64 operations,
                             // like the definition); for binary16 one fused fp64 operation is far inside the rounding
-                            if constexpr (DEQ == 1) y[c] = (float)(div * scale[c] + bsd[c]);
-                            else y[c] = (float)__builtin_fma(div, scale[c], bsd[c]);
+                            // (the variant with both fused epilogues is out of registers: it widens the bias here)
+                            const double bd = EPI == 3 ? (double)bs.f[c] : bsd[c];
+                            if constexpr (DEQ == 1) y[c] = (float)(div * scale[c] + bd);
+                            else y[c] = (float)__builtin_fma(div, scale[c], bd);
                             if constexpr (COLSUM) dsum[c] += div;
                         }
                         if constexpr (COLSUM) { rs_sum += (int)rs; ++rows_in; }
@@ -680,7 +689,6 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                                 }
                                 w ^= 0x80808080u;   // u - 128 as a byte
                                 rsy = __builtin_amdgcn_sdot4((int)w, 0x01010101, 0, false);
-                                ++cq_rows;
                                 *reinterpret_cast<uint32_t*>(yq_lane + t * kPanel) = w;
                             }
                         } else {
@@ -729,7 +737,7 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
             int cq[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                cq[c] = (int)cqf[c] - 128 * cq_rows;
+                cq[c] = (int)cqf[c] - 128 * rows_in;   // (the fused variants always carry the column sums: rows_in is counted)
                 cq[c] += partner<4>(cq[c]);
                 cq[c] += partner<5>(cq[c]);
             }
@@ -739,12 +747,12 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                     atomicAdd(reinterpret_cast<unsigned long long*>(&g.colsum_yq[n + c]), (unsigned long long)(long long)cq[c]);
             }
         }
-        if constexpr (EPI != 0) raise_status(g.status, est);
+        if constexpr (EPI != 0 || DEQ != 0) raise_status(g.status, est);
         if constexpr (COLSUM) {
             if constexpr (DEQ != 0) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    csum[c] = (long long)dsum[c] - (long long)rows_in * (long long)(int)cn[c] + (long long)(int)zw[c] * (long long)rs_sum;
+                    csum[c] = (long long)dsum[c] - (long long)rows_in * (long long)(int)cn[c] + (long long)zwv[c] * (long long)rs_sum;
             }
             // lanes l, l ^ 16, l ^ 32 hold the same channels for different tokens
 #pragma unroll
@@ -916,6 +924,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     g.act_step = act_step; g.act_zero = act_zero; g.step_w = step_w; g.zero_w = zero_w;
     g.rowsum_x = rowsum_x; g.rowsum_w = rowsum_w; g.bias = bias;
     clear_fused(g);
+    g.status = status;
     int64_t blocks = 0;
     const int prc = plan_gemm(g, T, N, K, blocks);
     if (prc != AWEQ_OK) return prc;

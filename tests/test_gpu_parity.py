@@ -551,6 +551,41 @@ def test_gemm_dequant_epilogue(B, orc, odt, K, N, T):
         assert np.all(np.abs(got - ref) <= ulp)
 
 
+@pytest.mark.parametrize("N", [260, 262])   # the tiled kernel / the generic kernel
+def test_gemm_dequant_zero_points_outside_the_code_range(B, orc, N):
+    """A slice whose range does not contain 0 has its zero point outside [0, 255] (Eq. 2 does not clamp
+    it).  The epilogue must still de-quantise exactly while the integer part fits 32 bits, and says so
+    in the status word."""
+    progress(f"gemm dequant epilogue, zero points outside [0, 255], N={N}")
+    rng = np.random.default_rng(12)
+    T, K = 300, 320
+    xq = rng.integers(-128, 128, (T, K), dtype=np.int8)
+    wq = rng.integers(-128, 128, (N, K), dtype=np.int8)
+    zero_w = rng.integers(90, 170, N).astype(np.int32)
+    zero_w[[0, 5, 70, 130, N - 1]] = [-40, 300, 1000, -3000, 256]
+    deq = dict(dtype=np.float32, step_x=0.0123, zero_x=141, step_w=rng.uniform(1e-4, 1e-3, N).astype(np.float32),
+               zero_w=zero_w, bias=rng.standard_normal(N).astype(np.float32),
+               rowsum_x=xq.astype(np.int64).sum(axis=1).astype(np.int32), rowsum_w=wq.astype(np.int64).sum(axis=1).astype(np.int32))
+    ref = orc.w8a8_output_direct(xq, wq, deq["step_x"], deq["zero_x"], deq["step_w"], deq["zero_w"], deq["bias"])
+    for odt in (np.float32, np.float16):
+        deq["dtype"] = odt
+        T_, K_ = xq.shape
+        out_deq = torch.zeros((T_, N), dtype=torch.float16 if odt == np.float16 else torch.float32, device=DEV)
+        cs = e(N, dtype=torch.int64)
+        status = torch.zeros(1, dtype=torch.int32, device=DEV)
+        B.aweq_w8a8_gemm(dev(to_panels(xq)), B.AWEQ_I8, T_, K_, K_, None, dev(np.array([deq["step_x"]], np.float32)),
+                         dev(np.array([deq["zero_x"]], np.int32)), None, dev(deq["rowsum_x"]), None, dev(to_panels(wq)), N,
+                         dev(deq["step_w"]), dev(deq["zero_w"]), dev(deq["rowsum_w"]), dev(deq["bias"]), None, out_deq,
+                         B.AWEQ_F16 if odt == np.float16 else B.AWEQ_F32, N, cs, None, status)
+        got = host(out_deq)
+        if odt == np.float32:
+            assert np.array_equal(got, ref.astype(np.float32))
+        else:
+            assert np.all(np.abs(got.astype(np.float64) - ref) <= np.maximum(np.abs(ref), 2.0 ** -14) * 2.0 ** -10)
+        assert np.array_equal(host(cs), orc.gemm_i8(xq, wq).astype(np.int64).sum(axis=0))
+        assert int(host(status)[0]) == B.ST_ZEROPOINT
+
+
 def test_gemm_with_activation_quantizer_in_front(B, orc):
     """aweq_w8a8_gemm with FP input runs stage 4a itself."""
     progress("gemm with fused call of stage 4a")
