@@ -618,6 +618,35 @@ def main():
     wall = time.perf_counter() - t0
 
     ms_per_step = wall * 1e3 / args.steps
+
+    # the same layers calibrated without the forward (outside the timed region of `value`): the bias
+    # correction takes the accumulator's sums over tokens from the weight codes, the activation
+    # quantizer only forms its sums
+    def calib_only_step():
+        for lin, X, W, b, buf in layers:
+            t, K, N, st = buf.t, lin.K, lin.N, buf.t["status"]
+            B.aweq_calib_stats(X, dt, T, K, K, t["xmin"], t["xmax"], t["xsum"], t["count"], 0, 1, t["r_x"], t["R_x"],
+                               t["p_x"], t["ws"], st)
+            B.aweq_calib_stats(W, dt, N, K, K, t["wmin"], t["wmax"], None, t["wcount"], 0, 1, t["r_w"], t["R_w"],
+                               t["p_w"], t["ws"], st)
+            B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, 1, t["s"], t["inv_s"], None,
+                            None, dt, N, K, None, t["xhat_range"], t["mu_xhat"], t["act_step"], t["act_zero"], st)
+            B.aweq_fold_quant_weight(W, dt, N, K, K, t["s"], t["W_hat"], 8, t["codes"], t["step_w"], t["zero_w"],
+                                     t["rowsum_w"], st)
+            B.aweq_quant_act(X, dt, T, K, K, t["inv_s"], t["act_step"], t["act_zero"], None, None, t["colsum_xq"], st)
+            B.aweq_bias_correct(B.BIAS_W8A8, t["W_hat"], dt, N, K, K, t["mu_xhat"], T, None, t["colsum_xq"],
+                                t["rowsum_w"], t["act_step"], t["act_zero"], t["codes"], 8, 0, t["step_w"], t["zero_w"], b,
+                                t["delta"], t["bias_out"], 1, None, st)
+
+    ref_bias = [buf.t["bias_out"].clone() for *_r, buf in layers]
+    calib_only_step()
+    torch.cuda.synchronize()
+    calib_same = all(torch.equal(r, buf.t["bias_out"]) for r, (*_r, buf) in zip(ref_bias, layers))
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        calib_only_step()
+    torch.cuda.synchronize()
+    calib_only_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     # per-stage device time from the events (ms, summed over steps)
     stage_ms = {s: [0.0] * len(layers) for s in stages}
     for k in range(args.steps):
@@ -690,6 +719,11 @@ def main():
                                      f"algorithmic {algorithmic_gb:.1f} GB: operands once + int32 output)",
                      "note": "int8 multiply-add = 2 ops (TOP/s); achieved = sum 2*T*N*K / sum of event-timed GEMM "
                              f"launches ({n_gemm} launches, avg {gemm_ms_total / n_gemm:.3f} ms)"},
+        "calibration_without_forward": {
+            "ms_per_step": calib_only_ms, "tokens_per_s_per_layer": T * len(layers) / (calib_only_ms * 1e-3),
+            "bias_identical_to_the_run_with_the_gemm": calib_same,
+            "note": "statistics, equalization, weight quantizer, sums-only activation quantizer, bias correction from "
+                    "wq . colsum_xq (exact): what a W8A8 calibration needs when the forward itself is not wanted"},
         "roofline_hbm_passes": hbm_passes,
         "layers": per_layer,
         "status_bits": status_bits,

@@ -149,7 +149,8 @@ int aweq_fold_quant_weight(const void* W, aweq_dtype dt, int64_t N, int64_t K, i
  * quantizer (Eq. 1 with b = 8) applied to X_hat = X * inv_s on the fly:
  * xq[t,k] = clamp(round((X[t,k] * inv_s[k]) / Step_x) + Z_x, 0, 255) - 128,
  * rowsum_x[T] = sum_k xq (int32, nullable), colsum_xq[K] = sum_t xq (int64, nullable).
- * xq is written in the K-panel layout (aweq_panel_bytes(T, K) bytes).
+ * xq is written in the K-panel layout (aweq_panel_bytes(T, K) bytes); xq = NULL computes the sums
+ * only (one read of X, nothing written per element: what a calibration without the forward needs).
  * act_step / act_zero are the device scalars aweq_equalize wrote. */
 int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx,
                    const float* inv_s, const float* act_step, const int32_t* act_zero,
@@ -212,7 +213,10 @@ int aweq_w8a8_gemm_fused(const int8_t* xq, int64_t T, int64_t K, const int8_t* w
  * subtracts E[y~ - y]).  enable_bc = 0 still writes delta but copies the bias unchanged.
  * mode AWEQ_BIAS_W8A8: mean FP output = W_hat mu_xhat (fp64 accumulation); mean int8-path
  *   output from colsum_acc, colsum_xq, rowsum_w, act_step/act_zero, step_w/zero_w[N]
- *   (exact integers), count = T.
+ *   (exact integers), count = T.  colsum_acc = NULL: the sums over tokens of the accumulator are
+ *   formed from the weight codes instead (codes = the 8-bit per-row / per-tensor codes in the
+ *   K-panel layout, bits = 8, group <= 0): sum_t acc[t,n] = sum_k wq[n,k] colsum_xq[k], the same
+ *   integers, so the correction can be calibrated without running the forward.
  * mode AWEQ_BIAS_WEIGHT_ONLY (Eq. 12-15): delta[n] = -sum_k (W~[n,k] - W_hat[n,k]) mu_xhat[k]
  *   with W~ de-quantised from codes / bits / group / step_w / zero_w as laid out by
  *   aweq_quant_weight.

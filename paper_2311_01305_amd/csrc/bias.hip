@@ -31,20 +31,24 @@ __device__ __forceinline__ void load_w8(const void* row, int64_t u, float x[8])
 // W8A8 (Eq. 11 with the int8 path as the quantised layer):
 //   mean_t y[t,n]  = sum_k W_hat[n,k] mu_xhat[k]
 //   sum_t  y~[t,n] = Step_x Step_w[n] (colsum_acc[n] - T Z'x rowsum_w[n] - Z'w[n] sum_k colsum_xq[k] + T K Z'x Z'w[n])
+// colsum_acc[n] = sum_t acc[t,n] comes from the GEMM, or - by the same linearity, as exact integers -
+// from the weight codes: sum_t sum_k xq[t,k] wq[n,k] = sum_k wq[n,k] colsum_xq[k] (wq given, colsum_acc NULL),
+// so that calibration does not have to run the forward.
 template <bool F16>
 __global__ __launch_bounds__(kBiasBlock) void bias_w8a8_kernel(
     const void* __restrict__ W_hat, int64_t K, int64_t ldw, const float* __restrict__ mu_xhat, uint64_t count,
     const long long* __restrict__ colsum_acc, const long long* __restrict__ colsum_xq,
     const int32_t* __restrict__ rowsum_w, const float* __restrict__ act_step, const int32_t* __restrict__ act_zero,
     const float* __restrict__ step_w, const int32_t* __restrict__ zero_w, const float* __restrict__ bias_in,
-    float* __restrict__ delta, float* __restrict__ bias_out, int enable_bc)
+    float* __restrict__ delta, float* __restrict__ bias_out, int enable_bc, const int8_t* __restrict__ wq)
 {
     __shared__ double slot_d[kBiasBlock / kWave];
     __shared__ long long slot_l[kBiasBlock / kWave];
     const int64_t n = blockIdx.x;
+    const int64_t N = gridDim.x;
     const char* row = reinterpret_cast<const char*>(W_hat) + (size_t)n * ldw * (F16 ? 2 : 4);
     double acc = 0.0;
-    long long tot = 0;
+    long long tot = 0, ca = 0;
     for (int64_t u = threadIdx.x; u < K / 8; u += kBiasBlock) {
         float w[8];
         load_w8<F16>(row, u, w);
@@ -55,16 +59,27 @@ __global__ __launch_bounds__(kBiasBlock) void bias_w8a8_kernel(
             acc += (double)w[i] * (double)m0.f[i];
             acc += (double)w[4 + i] * (double)m1.f[i];
         }
+        long long cx[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) tot += colsum_xq[u * 8 + i];
+        for (int i = 0; i < 8; ++i) { cx[i] = colsum_xq[u * 8 + i]; tot += cx[i]; }
+        if (wq) {
+            // unit u of row n in the K-panel layout: panel u / 8, bytes 8 (u % 8) ..
+            const uint2 v = *reinterpret_cast<const uint2*>(wq + ((u >> 3) * N + n) * kPanel + (u & 7) * 8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ca += (long long)(int8_t)((v.x >> (8 * i)) & 0xff) * cx[i];
+                ca += (long long)(int8_t)((v.y >> (8 * i)) & 0xff) * cx[4 + i];
+            }
+        }
     }
     acc = block_allreduce<kBiasBlock / kWave>(acc, OpAdd(), slot_d);
     tot = block_allreduce<kBiasBlock / kWave>(tot, OpAdd(), slot_l);
+    if (wq) ca = block_allreduce<kBiasBlock / kWave>(ca, OpAdd(), slot_l);
     if (threadIdx.x == 0) {
         const long long T = (long long)count;
         const long long zx = (long long)*act_zero - 128;
         const long long zw = (long long)zero_w[n] - 128;
-        const long long a = colsum_acc[n] - T * zx * (long long)rowsum_w[n] - zw * tot + T * K * zx * zw;
+        const long long a = (wq ? ca : colsum_acc[n]) - T * zx * (long long)rowsum_w[n] - zw * tot + T * K * zx * zw;
         const double yq = (double)*act_step * (double)step_w[n] * (double)a / (double)T;
         const double d = acc - yq;
         delta[n] = (float)d;
@@ -152,16 +167,21 @@ extern "C" int aweq_bias_correct(int mode, const void* W_hat, aweq_dtype dt, int
     hipStream_t st = as_stream(stream);
     const bool f16 = dt == AWEQ_F16;
     if (mode == AWEQ_BIAS_W8A8) {
-        if (!colsum_acc || !colsum_xq || !rowsum_w || !act_step || !act_zero) return AWEQ_ERR_NULL;
+        if (!colsum_xq || !rowsum_w || !act_step || !act_zero) return AWEQ_ERR_NULL;
+        if (!colsum_acc && !codes) return AWEQ_ERR_NULL;
         if (count == 0) return AWEQ_ERR_SHAPE;
+        // without the GEMM's column sums they are formed from the 8-bit per-row / per-tensor codes (K-panel layout)
+        const int8_t* wq = colsum_acc ? nullptr : reinterpret_cast<const int8_t*>(codes);
+        if (wq && (bits != 8 || group > 0)) return AWEQ_ERR_BITS;
+        if (wq && !aligned16(wq)) return AWEQ_ERR_ALIGN;
         const long long* ca = reinterpret_cast<const long long*>(colsum_acc);
         const long long* cx = reinterpret_cast<const long long*>(colsum_xq);
         if (f16)
             bias_w8a8_kernel<true><<<(unsigned)N, kBiasBlock, 0, st>>>(W_hat, K, ldw, mu_xhat, count, ca, cx, rowsum_w, act_step,
-                                                                     act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc);
+                                                                     act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc, wq);
         else
             bias_w8a8_kernel<false><<<(unsigned)N, kBiasBlock, 0, st>>>(W_hat, K, ldw, mu_xhat, count, ca, cx, rowsum_w, act_step,
-                                                                      act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc);
+                                                                      act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc, wq);
     } else if (mode == AWEQ_BIAS_WEIGHT_ONLY) {
         if (!codes) return AWEQ_ERR_NULL;
         if (bits != 8 && bits != 4 && bits != 3) return AWEQ_ERR_BITS;

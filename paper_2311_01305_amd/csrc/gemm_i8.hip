@@ -791,7 +791,7 @@ int launch_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t
                      const float* act_step, const int32_t* act_zero, int8_t* xq, int32_t* rowsum_x,
                      int64_t* colsum_xq, uint32_t* status, hipStream_t st);
 int check_quant_act_args(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx, const float* inv_s,
-                         const float* act_step, const int32_t* act_zero, const int8_t* xq);
+                         const float* act_step, const int32_t* act_zero, const int8_t* xq, bool xq_optional);
 
 }  // namespace aweq
 
@@ -898,7 +898,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
         if (ldx != K) return AWEQ_ERR_SHAPE;
         a = reinterpret_cast<const int8_t*>(X);
     } else {
-        const int rc = check_quant_act_args(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq);
+        const int rc = check_quant_act_args(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq, false);
         if (rc != AWEQ_OK) return rc;
         a = xq;
     }

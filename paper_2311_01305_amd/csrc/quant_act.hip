@@ -109,7 +109,7 @@ __device__ __forceinline__ void act_unit(const float x[8], const float is[8], co
     rs = __builtin_amdgcn_sdot4((int)w[0], 0x01010101, rs, false);
     rs = __builtin_amdgcn_sdot4((int)w[1], 0x01010101, rs, false);
     typedef unsigned v2u_ __attribute__((ext_vector_type(2)));
-    __builtin_nontemporal_store(v2u_{w[0], w[1]}, reinterpret_cast<v2u_*>(dst));
+    if (dst) __builtin_nontemporal_store(v2u_{w[0], w[1]}, reinterpret_cast<v2u_*>(dst));   // (sums only: no code buffer)
 }
 
 // 8 consecutive input values of one row as loaded (binary16: one 16-byte quad), converted to
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
 
     const int64_t panel0 = (int64_t)chunk * kQaPanels + wave * kQaVpt;
     const int col0 = (int)(panel0 * kPanel) + c8 * 8;                      // K <= 2^31 - 1 columns
-    int8_t* const dst0 = xq + (panel0 * T + r0) * kPanel + c8 * 8;         // this lane's 8 bytes of row r0, panel j = 0
+    int8_t* const dst0 = xq ? xq + (panel0 * T + r0) * kPanel + c8 * 8 : nullptr;   // this lane's 8 bytes of row r0, panel j = 0
     const int64_t dst_step = T * kPanel;                                   // to the next panel
     const char* const src0 = reinterpret_cast<const char*>(X) + (r0 * ldx + col0) * (F16 ? 2 : 4);
     bool valid[kQaVpt], pad[kQaVpt];
@@ -230,12 +230,12 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
                     ++my_rows;
 #pragma unroll
                     for (int j = 0; j < kQaVpt; ++j) {
-                        int8_t* d = dst0 + j * dst_step + row * kPanel;
+                        int8_t* d = dst0 ? dst0 + j * dst_step + row * kPanel : nullptr;
                         if (valid[j]) {
                             float x[8];
                             raw[b][j].get(x);
                             act_unit<MODE>(x, is[j], p, d, csf[j], csi[j], rs, big, st);
-                        } else if (pad[j]) {
+                        } else if (pad[j] && d) {
                             *reinterpret_cast<uint2*>(d) = make_uint2(0u, 0u);
                         }
                     }
@@ -312,9 +312,9 @@ int launch_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t
 }
 
 int check_quant_act_args(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx, const float* inv_s,
-                         const float* act_step, const int32_t* act_zero, const int8_t* xq)
+                         const float* act_step, const int32_t* act_zero, const int8_t* xq, bool xq_optional)
 {
-    if (!X || !inv_s || !act_step || !act_zero || !xq) return AWEQ_ERR_NULL;
+    if (!X || !inv_s || !act_step || !act_zero || (!xq && !xq_optional)) return AWEQ_ERR_NULL;
     if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
     if (T <= 0 || K <= 0 || ldx < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
     if (!aligned16(X) || ((size_t)ldx * dtype_size(dt)) % 16 != 0 || !aligned16(xq)) return AWEQ_ERR_ALIGN;
@@ -330,7 +330,8 @@ extern "C" int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K
                               int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
                               uint32_t* status, void* stream)
 {
-    const int rc = check_quant_act_args(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq);
+    if (!xq && !rowsum_x && !colsum_xq) return AWEQ_ERR_NULL;   // nothing to produce
+    const int rc = check_quant_act_args(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, true);
     if (rc != AWEQ_OK) return rc;
     return launch_quant_act(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, status, as_stream(stream));
 }

@@ -74,9 +74,12 @@ class LayerBuffers:
 
 
 def calibrate_layer(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], buf: LayerBuffers,
-                    enable_awe: bool = True, enable_bc: bool = True, stream=None, fused_weight_pass: bool = False):
+                    enable_awe: bool = True, enable_bc: bool = True, stream=None, fused_weight_pass: bool = False,
+                    forward: bool = True):
     """One pass of the whole hot path for one linear layer.  Everything is enqueued on the
-    current (or given) stream; nothing synchronises."""
+    current (or given) stream; nothing synchronises.  forward = False (W8A8) calibrates without
+    running the int8 GEMM: the activation quantizer only forms its sums and the bias correction
+    takes the accumulator's sums over tokens from the weight codes (the same integers)."""
     t = buf.t
     T, K, N = buf.T, buf.K, buf.N
     dt = _dt(X)
@@ -102,7 +105,13 @@ def calibrate_layer(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tenso
         # per-tensor weights (Sec. 3): the one (Step, Z) is repeated for every output channel (a copy)
         t["step_w"][1:].copy_(t["step_w"][0].expand(N - 1))
         t["zero_w"][1:].copy_(t["zero_w"][0].expand(N - 1))
-    if buf.w8a8:
+    if buf.w8a8 and not forward:
+        B.aweq_quant_act(X, dt, T, K, X.stride(0), t["inv_s"], t["act_step"], t["act_zero"], None, None, t["colsum_xq"],
+                         st, stream)
+        B.aweq_bias_correct(B.BIAS_W8A8, t["W_hat"], dt, N, K, K, t["mu_xhat"], T, None, t["colsum_xq"], t["rowsum_w"],
+                            t["act_step"], t["act_zero"], t["codes"], 8, 0, t["step_w"], t["zero_w"], bias, t["delta"],
+                            t["bias_out"], enable_bc, None, st, stream)
+    elif buf.w8a8:
         # stage 4: activation quantizer + int8 GEMM (+ per-channel output sums for stage 5)
         B.aweq_w8a8_gemm(X, dt, T, K, X.stride(0), t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],
                          t["colsum_xq"], t["codes"], N, t["step_w"], t["zero_w"], t["rowsum_w"], bias,

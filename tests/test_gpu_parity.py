@@ -720,3 +720,38 @@ def test_end_to_end_unforced(B, orc, cfg, T, shapes):
         resid = (y_q + host(t["delta"]).astype(np.float64) - y_fp).mean(axis=0)
         assert np.max(np.abs(resid)) <= 2e-5 * np.max(np.abs(d_ref)) + 1e-6 * np.max(np.abs(y_fp.mean(axis=0)))
         assert int(host(t["status"])[0]) == 0
+
+
+@pytest.mark.parametrize("dtype,T,K,N,has_bias", [(np.float16, 700, 1032, 260, True), (np.float32, 300, 512, 64, False)])
+def test_calibration_without_the_forward(B, orc, dtype, T, K, N, has_bias):
+    """Bias correction needs only the sum over tokens of the accumulator, and that is the weight
+    codes times the column sums of the activation codes (exact integers): the layer calibrated with
+    the GEMM skipped and a sums-only activation quantizer must give bit-identical delta and bias."""
+    from paper_2311_01305_amd import pipeline
+    progress(f"calibration without the forward {dtype.__name__} T={T} K={K} N={N}")
+    rng = np.random.default_rng(T + K)
+    X, W = make_layer(rng, dtype, T, K, N, outliers=(3, 60))
+    b = (rng.standard_normal(N) * 0.02).astype(np.float32) if has_bias else None
+    tdt = torch.float16 if dtype == np.float16 else torch.float32
+    res = []
+    for forward in (True, False):
+        buf = pipeline.LayerBuffers(T, K, N, tdt, want_out_i32=forward, want_out_deq=False)
+        t = pipeline.calibrate_layer(dev(X), dev(W), dev(b) if b is not None else None, buf, forward=forward)
+        res.append({k: host(t[k]) for k in ("delta", "bias_out", "colsum_xq", "rowsum_w", "codes", "mu_xhat", "act_step",
+                                            "act_zero", "step_w", "zero_w", "W_hat", "status")})
+    full, lean = res
+    for k in ("delta", "bias_out", "colsum_xq"):
+        assert np.array_equal(full[k].view(np.uint8), lean[k].view(np.uint8)), k
+    assert int(lean["status"][0]) == int(full["status"][0])
+    # and against the oracle's identity route
+    wq = from_panels(lean["codes"], N, K)
+    ca = orc.colsum_acc_from_colsum_xq(wq, lean["colsum_xq"])
+    d_ref, b_ref = orc.bias_w8a8(lean["W_hat"], lean["mu_xhat"], T, ca, lean["colsum_xq"], lean["rowsum_w"], lean["act_step"][0],
+                                 int(lean["act_zero"][0]), lean["step_w"], lean["zero_w"], b)
+    assert np.max(np.abs(lean["delta"] - d_ref)) <= 1e-5 * np.max(np.abs(d_ref))
+    np.testing.assert_allclose(lean["bias_out"], b_ref, rtol=1e-5, atol=1e-5 * np.max(np.abs(d_ref)))
+    # the sums-only activation quantizer alone
+    rs, cs = e(T, dtype=torch.int32), e(K, dtype=torch.int64)
+    B.aweq_quant_act(dev(X), dtc(B, X), T, K, K, dev(host(t["inv_s"])), t["act_step"], t["act_zero"], None, rs, cs)
+    a = orc.quant_act(X, host(t["inv_s"]), lean["act_step"][0], int(lean["act_zero"][0]))
+    assert np.array_equal(host(rs), a["rowsum_x"]) and np.array_equal(host(cs), a["colsum_xq"])

@@ -129,6 +129,7 @@ def test_gemm_and_quant_act_argument_errors(B):
     qa = dict(X=P, dt=B.AWEQ_F16, T=8, K=64, ldx=64, inv_s=P, act_step=P, act_zero=P, xq=P, rowsum_x=None, colsum_xq=None)
     qcall = lambda **kw: B.aweq_quant_act(**{**qa, **kw})
     assert _code(qcall, act_step=None) == "AWEQ_ERR_NULL"
+    assert _code(qcall, xq=None) == "AWEQ_ERR_NULL"           # no codes and no sums asked for: nothing to do
     assert _code(qcall, dt=B.AWEQ_I8) == "AWEQ_ERR_DTYPE"
     assert _code(qcall, X=P + 8) == "AWEQ_ERR_ALIGN"
 
@@ -138,7 +139,9 @@ def test_bias_correct_argument_errors(B):
               colsum_xq=P, rowsum_w=P, act_step=P, act_zero=P, codes=None, bits=8, group=0, step_w=P, zero_w=P,
               bias_in=None, delta=P, bias_out=P, enable_bc=1)
     call = lambda **kw: B.aweq_bias_correct(**{**ok, **kw})
-    assert _code(call, colsum_acc=None) == "AWEQ_ERR_NULL"
+    assert _code(call, colsum_acc=None) == "AWEQ_ERR_NULL"          # neither the GEMM's sums nor the codes to form them from
+    assert _code(call, colsum_acc=None, codes=P, bits=4) == "AWEQ_ERR_BITS"
+    assert _code(call, colsum_acc=None, codes=P, group=128) == "AWEQ_ERR_BITS"
     assert _code(call, count=0) == "AWEQ_ERR_SHAPE"
     assert _code(call, mode=7) == "AWEQ_ERR_SHAPE"
     assert _code(call, mode=B.BIAS_WEIGHT_ONLY) == "AWEQ_ERR_NULL"  # needs codes
