@@ -100,6 +100,21 @@ int aweq_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int6
                      int accumulate, int finalize, float* r, float* R, float* p,
                      void* ws, size_t ws_bytes, uint32_t* status, void* stream);
 
+/* ---- Stage 1 for callers that cannot allocate or pass scratch memory (code under HIP graph capture
+ * with a fixed argument list, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and results as aweq_calib_stats, with the per-slice partial rows kept in a device array of
+ * AWEQ_STATIC_SCRATCH_BYTES that is part of the library (every GPU the library runs on holds one
+ * copy until the process ends) instead of a caller's workspace.  The call allocates nothing.
+ * AWEQ_ERR_WORKSPACE when aweq_workspace_size(AWEQ_OP_CALIB_STATS, rows, K, 0) exceeds
+ * AWEQ_STATIC_SCRATCH_BYTES (all configurations up to 262144 x 22016 binary16 fit).  The device
+ * that owns `stream` must be the current device.  All calls on one GPU share that GPU's array:
+ * calls that overlap on one GPU (different streams) race; calls on one stream do not. */
+#define AWEQ_STATIC_SCRATCH_BYTES (16u << 20)
+int aweq_calib_stats_static(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int64_t ld,
+                            float* cmin, float* cmax, double* csum, uint64_t* count,
+                            int accumulate, int finalize, float* r, float* R, float* p,
+                            uint32_t* status, void* stream);
+
 /* ---- Stage 2: activation-weight equalization (Sec. 3.1 Eq. 3, Sec. 3.2 Eq. 10).
  * From the column statistics of X (xmin, xmax, xsum, host scalar count = T) and of W
  * (wmin, wmax): s[k] = sqrt(r_x r_w) / r_w evaluated in fp64 on the raw channel ranges,

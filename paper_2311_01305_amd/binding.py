@@ -19,7 +19,9 @@ ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD, ST_ZEROPOINT = 1, 2, 4, 
 
 EXPORTS = ("aweq_workspace_size", "aweq_status_string", "aweq_calib_stats", "aweq_equalize",
            "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock",
-           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8", "aweq_wonly_gemm", "aweq_fold_quant_weight", "aweq_w8a8_gemm_fused")
+           "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8", "aweq_wonly_gemm", "aweq_fold_quant_weight", "aweq_w8a8_gemm_fused",
+           "aweq_calib_stats_static")
+STATIC_SCRATCH_BYTES = 16 << 20
 
 _vp, _i64, _i32, _u64, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_float, C.c_size_t
 
@@ -50,6 +52,9 @@ def load_library():
     lib.aweq_calib_stats.restype = _i32
     lib.aweq_calib_stats.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
                                      _vp, _sz, _vp, _vp]
+    lib.aweq_calib_stats_static.restype = _i32
+    lib.aweq_calib_stats_static.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
+                                            _vp, _vp]
     lib.aweq_equalize.restype = _i32
     lib.aweq_equalize.argtypes = [_vp, _vp, _vp, _u64, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _i32, _i64, _i64,
                                   _vp, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -123,6 +128,13 @@ def aweq_calib_stats(M, dt, rows, K, ld, cmin, cmax, csum, count, accumulate, fi
         _ptr(M), dt, rows, K, ld, _ptr(cmin), _ptr(cmax), _ptr(csum), _ptr(count), int(accumulate), int(finalize),
         _ptr(r), _ptr(R), _ptr(p), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes, _ptr(status),
         _stream(stream)))
+
+
+def aweq_calib_stats_static(M, dt, rows, K, ld, cmin, cmax, csum, count, accumulate, finalize, r, R, p,
+                            status=None, stream=None):
+    _check(load_library().aweq_calib_stats_static(
+        _ptr(M), dt, rows, K, ld, _ptr(cmin), _ptr(cmax), _ptr(csum), _ptr(count), int(accumulate), int(finalize),
+        _ptr(r), _ptr(R), _ptr(p), _ptr(status), _stream(stream)))
 
 
 def aweq_equalize(xmin, xmax, xsum, count, wmin, wmax, K, enable_awe, s, inv_s, W, W_hat, dt, N, ldw,

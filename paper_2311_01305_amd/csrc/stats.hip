@@ -7,6 +7,7 @@
 // (min, max, sum) to the workspace, and a second small kernel folds the slices in a fixed
 // order (so the fp64 sums are reproducible) and merges with earlier batches.
 #include "common.hpp"
+#include <atomic>
 
 namespace aweq {
 
@@ -266,25 +267,12 @@ __global__ __launch_bounds__(1024) void col_stats_finalize(
 
 size_t stats_ws_bytes_export(int64_t rows, int64_t K) { return stats_ws_bytes(rows, K); }
 
-}  // namespace aweq
-
-using namespace aweq;
-
-extern "C" int aweq_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int64_t ld,
-                                float* cmin, float* cmax, double* csum, uint64_t* count,
-                                int accumulate, int finalize, float* r, float* R, float* p,
-                                void* ws, size_t ws_bytes, uint32_t* status, void* stream)
+// the statistics pass on a workspace that is known to be large enough and 16-byte aligned
+static int run_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int64_t ld,
+                           float* cmin, float* cmax, double* csum, uint64_t* count,
+                           int accumulate, int finalize, float* r, float* R, float* p,
+                           void* ws, uint32_t* status, hipStream_t st)
 {
-    if (!M || !cmin || !cmax) return AWEQ_ERR_NULL;
-    if (finalize && (!r || !R)) return AWEQ_ERR_NULL;
-    if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
-    if (rows <= 0 || K <= 0 || ld < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
-    const size_t es = dtype_size(dt);
-    if (!aligned16(M) || ((size_t)ld * es) % 16 != 0) return AWEQ_ERR_ALIGN;
-    if (!ws || ws_bytes < stats_ws_bytes(rows, K)) return AWEQ_ERR_WORKSPACE;
-    if (!aligned16(ws)) return AWEQ_ERR_ALIGN;
-
-    hipStream_t st = as_stream(stream);
     const int epl = dt == AWEQ_F16 ? 8 : 4;
     const StatsPlan plan = stats_plan(rows, K, epl);
     // workspace layout: psum (fp64) first, then pmin, pmax
@@ -302,4 +290,72 @@ extern "C" int aweq_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int6
                                                             csum, count, accumulate, status);
     if (finalize) col_stats_finalize<<<1, 1024, 0, st>>>(cmin, cmax, K, r, R, p);
     return launch_status();
+}
+
+static int check_calib_stats_args(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int64_t ld,
+                                  const float* cmin, const float* cmax, int finalize, const float* r, const float* R)
+{
+    if (!M || !cmin || !cmax) return AWEQ_ERR_NULL;
+    if (finalize && (!r || !R)) return AWEQ_ERR_NULL;
+    if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
+    if (rows <= 0 || K <= 0 || ld < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
+    if (!aligned16(M) || ((size_t)ld * dtype_size(dt)) % 16 != 0) return AWEQ_ERR_ALIGN;
+    return AWEQ_OK;
+}
+
+// ---- scratch of the entry point that may not allocate: the per-slice partial rows live in a
+// file-scope device array instead of a caller's workspace.  Every GPU the library runs on holds
+// its own copy of the array (at its own address) until the process ends.
+constexpr size_t kStaticScratchBytes = AWEQ_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_of_device[kMaxDevices];
+
+// device address of `scratch` on the current device (looked up once per device; in host code the
+// array's name is only a handle for this lookup, never an address a kernel may be given)
+static int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return AWEQ_ERR_LAUNCH;
+    void* ptr = g_scratch_of_device[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return AWEQ_ERR_LAUNCH;
+        g_scratch_of_device[dev].store(ptr, std::memory_order_release);   // (a racing thread stores the same address)
+    }
+    *out = ptr;
+    return AWEQ_OK;
+}
+
+}  // namespace aweq
+
+using namespace aweq;
+
+extern "C" int aweq_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int64_t ld,
+                                float* cmin, float* cmax, double* csum, uint64_t* count,
+                                int accumulate, int finalize, float* r, float* R, float* p,
+                                void* ws, size_t ws_bytes, uint32_t* status, void* stream)
+{
+    const int rc = check_calib_stats_args(M, dt, rows, K, ld, cmin, cmax, finalize, r, R);
+    if (rc != AWEQ_OK) return rc;
+    if (!ws || ws_bytes < stats_ws_bytes(rows, K)) return AWEQ_ERR_WORKSPACE;
+    if (!aligned16(ws)) return AWEQ_ERR_ALIGN;
+    return run_calib_stats(M, dt, rows, K, ld, cmin, cmax, csum, count, accumulate, finalize, r, R, p, ws, status,
+                           as_stream(stream));
+}
+
+extern "C" int aweq_calib_stats_static(const void* M, aweq_dtype dt, int64_t rows, int64_t K, int64_t ld,
+                                       float* cmin, float* cmax, double* csum, uint64_t* count,
+                                       int accumulate, int finalize, float* r, float* R, float* p,
+                                       uint32_t* status, void* stream)
+{
+    const int rc = check_calib_stats_args(M, dt, rows, K, ld, cmin, cmax, finalize, r, R);
+    if (rc != AWEQ_OK) return rc;
+    if (stats_ws_bytes(rows, K) > kStaticScratchBytes) return AWEQ_ERR_WORKSPACE;   // beyond the built-in scratch
+    void* ptr = nullptr;
+    const int src = static_scratch(&ptr);
+    if (src != AWEQ_OK) return src;
+    // every partial row the merge reads is written by this call's first kernel: nothing to clear
+    return run_calib_stats(M, dt, rows, K, ld, cmin, cmax, csum, count, accumulate, finalize, r, R, p, ptr, status,
+                           as_stream(stream));
 }

@@ -82,6 +82,25 @@ def test_calib_stats_argument_errors(B):
     assert _code(call, ws_bytes=16) == "AWEQ_ERR_WORKSPACE"
 
 
+def test_calib_stats_static_argument_errors(B):
+    """The entry point without a workspace argument: the same host checks, and a size limit instead
+    of a workspace check (found before anything touches the GPU)."""
+    ok = dict(M=P, dt=B.AWEQ_F16, rows=64, K=64, ld=64, cmin=P, cmax=P, csum=P, count=P, accumulate=0, finalize=1,
+              r=P, R=P, p=P, stream=0)
+    call = lambda **kw: B.aweq_calib_stats_static(**{**ok, **kw})
+    assert _code(call, M=None) == "AWEQ_ERR_NULL"
+    assert _code(call, R=None) == "AWEQ_ERR_NULL"
+    assert _code(call, dt=B.AWEQ_I8) == "AWEQ_ERR_DTYPE"
+    assert _code(call, K=60, ld=60) == "AWEQ_ERR_SHAPE"
+    assert _code(call, M=P + 2) == "AWEQ_ERR_ALIGN"
+    big = 1 << 21
+    assert B.aweq_workspace_size(B.OP_CALIB_STATS, big, big) > B.STATIC_SCRATCH_BYTES
+    assert _code(call, rows=big, K=big, ld=big) == "AWEQ_ERR_WORKSPACE"
+    # every configuration of the benchmark fits
+    for K in (4096, 8192, 11008, 16384, 22016):
+        assert B.aweq_workspace_size(B.OP_CALIB_STATS, 262144, K) <= B.STATIC_SCRATCH_BYTES
+
+
 def test_equalize_argument_errors(B):
     ok = dict(xmin=P, xmax=P, xsum=P, count=10, wmin=P, wmax=P, K=64, enable_awe=1, s=P, inv_s=P, W=P, W_hat=P,
               dt=B.AWEQ_F16, N=8, ldw=64, prev_scale=None, xhat_range=P, mu_xhat=P, act_step=P, act_zero=P)
