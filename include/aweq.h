@@ -14,7 +14,8 @@
  *   - the library allocates nothing, frees nothing and never synchronises: each call
  *     enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default stream)
  *     and returns; scratch memory comes from the caller (`ws`, `ws_bytes`; ask
- *     aweq_workspace_size), and may be reused by the next call on the same stream;
+ *     aweq_workspace_size; 16-byte aligned; its contents need no initialisation), and may be
+ *     reused by the next call on the same stream; entry points without a `ws` argument need none;
  *   - the return value is 0 or a negative AWEQ_ERR_* code found on the HOST before
  *     anything is launched (bad pointer, shape, dtype, alignment, workspace);
  *   - numeric conditions met on the device are OR-ed into the optional device word
@@ -61,10 +62,20 @@ typedef enum {
     AWEQ_OP_QUANT_WEIGHT = 2,
     AWEQ_OP_W8A8_GEMM = 3,
     AWEQ_OP_BIAS_CORRECT = 4,
-    AWEQ_OP_WONLY_GEMM = 5
+    AWEQ_OP_WONLY_GEMM = 5,
+    AWEQ_OP_QUANT_ACT = 6
 } aweq_op;
 
 enum { AWEQ_BIAS_W8A8 = 0, AWEQ_BIAS_WEIGHT_ONLY = 1 };
+
+/* values of aweq_equalize's enable_awe */
+enum {
+    AWEQ_SCALE_NONE = 0,   /* s = 1: equalization off (the ablation of Sec. 4.4) */
+    AWEQ_SCALE_RANGE = 1,  /* Eq. 10 on the channel ranges: the method */
+    AWEQ_SCALE_ABSMAX = 2  /* Eq. 10's form on the channels' maximum absolute values instead of their ranges: the
+                              difficulty definition the method replaces (Sec. 1, Sec. 3.2), kept as a switch for
+                              comparisons on the same layers */
+};
 
 /* Bytes of workspace the op needs for a [rows x K] input (rows = T or N as the op reads
  * it) and N output channels; 0 when it needs none.  Host function, no GPU needed. */
@@ -118,10 +129,12 @@ int aweq_calib_stats_static(const void* M, aweq_dtype dt, int64_t rows, int64_t 
 /* ---- Stage 2: activation-weight equalization (Sec. 3.1 Eq. 3, Sec. 3.2 Eq. 10).
  * From the column statistics of X (xmin, xmax, xsum, host scalar count = T) and of W
  * (wmin, wmax): s[k] = sqrt(r_x r_w) / r_w evaluated in fp64 on the raw channel ranges,
- * inv_s[k] = 1 / s[k]  (enable_awe = 0: s = 1, the ablation switch of Sec. 4.4).
+ * inv_s[k] = 1 / s[k]  (enable_awe = AWEQ_SCALE_RANGE; AWEQ_SCALE_NONE: s = 1, the ablation switch of
+ * Sec. 4.4; AWEQ_SCALE_ABSMAX: the same formula with m = max(|min|, |max|) of the channel in place of r).
  * Guards: a channel with r_x < 1e-5 or r_w < 1e-5 gets s = 1; s is clamped to [1e-4, 1e4].
  * Fold, weight side: W_hat[n,k] = W[n,k] * s[k], one fp32 multiply rounded to dt
- * (W_hat may alias W; W = NULL skips the fold).  Activation side: the equalised
+ * (W has pitch ldw, W_hat pitch ldwh; W_hat may alias W when the pitches agree; W = NULL skips the
+ * fold).  Activation side: the equalised
  * activation X_hat[t,k] = X[t,k] * inv_s[k] is never stored; its tensor range
  * xhat_range[2] = {min, max}, its mean mu_xhat[K] = (xsum / count) * inv_s and the static
  * int8 activation quantizer derived from that range by Eq. 2 (act_step[1], act_zero[1])
@@ -130,7 +143,7 @@ int aweq_calib_stats_static(const void* M, aweq_dtype dt, int64_t rows, int64_t 
 int aweq_equalize(const float* xmin, const float* xmax, const double* xsum, uint64_t count,
                   const float* wmin, const float* wmax, int64_t K, int enable_awe,
                   float* s, float* inv_s,
-                  const void* W, void* W_hat, aweq_dtype dt, int64_t N, int64_t ldw,
+                  const void* W, void* W_hat, aweq_dtype dt, int64_t N, int64_t ldw, int64_t ldwh,
                   float* prev_scale, float* xhat_range, float* mu_xhat,
                   float* act_step, int32_t* act_zero,
                   uint32_t* status, void* stream);
@@ -153,11 +166,11 @@ int aweq_quant_weight(const void* W_hat, aweq_dtype dt, int64_t N, int64_t K, in
                       uint32_t* status, void* stream);
 
 /* ---- Stages 2b + 3 in one pass over W (per-row quantizer, group = 0): W_hat[n,k] = W[n,k] * s[k]
- * rounded to dt (Eq. 3; W_hat has W's pitch and may alias W) is written and quantised from registers,
+ * rounded to dt (Eq. 3; W_hat has pitch ldwh and may alias W when ldwh = ldw) is written and quantised from registers,
  * with the outputs of aweq_quant_weight(group = 0).  Same results as aweq_equalize's fold followed by
  * aweq_quant_weight; call aweq_equalize with W = NULL for the scales first. */
 int aweq_fold_quant_weight(const void* W, aweq_dtype dt, int64_t N, int64_t K, int64_t ldw,
-                           const float* s, void* W_hat, int bits, void* codes, float* step,
+                           const float* s, void* W_hat, int64_t ldwh, int bits, void* codes, float* step,
                            int32_t* zero, int32_t* rowsum_w, uint32_t* status, void* stream);
 
 /* ---- Stage 4a (helper, also run by aweq_w8a8_gemm): static per-tensor int8 activation
@@ -166,11 +179,16 @@ int aweq_fold_quant_weight(const void* W, aweq_dtype dt, int64_t N, int64_t K, i
  * rowsum_x[T] = sum_k xq (int32, nullable), colsum_xq[K] = sum_t xq (int64, nullable).
  * xq is written in the K-panel layout (aweq_panel_bytes(T, K) bytes); xq = NULL computes the sums
  * only (one read of X, nothing written per element: what a calibration without the forward needs).
- * act_step / act_zero are the device scalars aweq_equalize wrote. */
+ * act_step / act_zero are the device scalars aweq_equalize wrote.  The sums are formed without
+ * atomics, in a fixed order: per-slice partial sums in the workspace
+ * (aweq_workspace_size(AWEQ_OP_QUANT_ACT, T, K, 0) bytes; needed when colsum_xq is asked for, or
+ * rowsum_x with K > 512) and a merge kernel.  AWEQ_ST_BIGQUOT: some |X_hat / Step| reached 2^24
+ * (Step and Z not from this data); the quotient is then rounded, saturated at +-2^30, and clamped
+ * as Eq. 1 says. */
 int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx,
                    const float* inv_s, const float* act_step, const int32_t* act_zero,
                    int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
-                   uint32_t* status, void* stream);
+                   void* ws, size_t ws_bytes, uint32_t* status, void* stream);
 
 /* ---- Stage 4: W8A8 forward (Sec. 1-2: INT8 weights and activations).
  * x_dt F16 / F32: X is quantised into xq[T x K] first (stage 4a; xq, inv_s, act_step,
@@ -184,13 +202,17 @@ int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t l
  *   The integer in parentheses is formed in 32-bit arithmetic: exact whenever it fits, which zero
  *   points in [0, 255] (ranges that contain 0) guarantee for K <= 32768; other zero points are
  *   handled the same way and raise AWEQ_ST_ZEROPOINT;
- * colsum_acc[N] = sum_t acc[t,n] (int64; what stage 5 needs).
- * step_w / zero_w / rowsum_w are indexed by output channel here and in aweq_bias_correct (W8A8
- * mode): for a per-tensor weight quantizer (group = -1) pass the one (Step, Z) repeated N times. */
+ * colsum_acc[N] = sum_t acc[t,n] (int64; what stage 5 needs; always the sum of the accumulator
+ *   itself, whatever the zero points).
+ * w_group = 0: step_w[N] / zero_w[N] hold one entry per output channel (stage 3 with group = 0);
+ * w_group = -1: step_w[1] / zero_w[1], one for the tensor (stage 3 with group = -1, the paper's
+ * per-tensor setting, Sec. 3); rowsum_w[N] is per output channel in both cases.
+ * ws: the workspace of stage 4a when X is F16 / F32 (aweq_workspace_size(AWEQ_OP_W8A8_GEMM, T, K, N));
+ * not needed (NULL) for x_dt = I8. */
 int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t K, int64_t ldx,
                    const float* inv_s, const float* act_step, const int32_t* act_zero,
                    int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
-                   const int8_t* wq, int64_t N, const float* step_w, const int32_t* zero_w,
+                   const int8_t* wq, int64_t N, const float* step_w, const int32_t* zero_w, int w_group,
                    const int32_t* rowsum_w, const float* bias,
                    int32_t* out_i32, void* out_deq, aweq_dtype out_dt, int64_t ldo,
                    int64_t* colsum_acc, void* ws, size_t ws_bytes,
@@ -199,7 +221,7 @@ int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t K, int64_t
 /* ---- Stage 4 with fused epilogues for the layer that consumes this one's output (statistics of
  * Sec. 3.2 / Sec. 3.3's E[x] and the quantizer of Eq. 1 applied where the output is produced
  * instead of in passes of their own over it).  The GEMM and the de-quantisation are those of
- * aweq_w8a8_gemm with x_dt = I8; y[t,n] = act(de-quantised output + bias) rounded to binary16,
+ * aweq_w8a8_gemm with x_dt = I8 and w_group = 0 (per-channel weight scales); y[t,n] = act(de-quantised output + bias) rounded to binary16,
  * act = 0 (none) or 1 (ReLU, OPT's fc1 -> fc2).  Outputs:
  *  out_f16[T x N] (pitch ldo, nullable): y itself;
  *  colsum_acc[N] (required): as in aweq_w8a8_gemm, for this layer's stage 5;
@@ -227,8 +249,8 @@ int aweq_w8a8_gemm_fused(const int8_t* xq, int64_t T, int64_t K, const int8_t* w
  * minus the mean output of the quantised layer; bias_out = bias_in + delta (the paper
  * subtracts E[y~ - y]).  enable_bc = 0 still writes delta but copies the bias unchanged.
  * mode AWEQ_BIAS_W8A8: mean FP output = W_hat mu_xhat (fp64 accumulation); mean int8-path
- *   output from colsum_acc, colsum_xq, rowsum_w, act_step/act_zero, step_w/zero_w[N]
- *   (exact integers), count = T.  colsum_acc = NULL: the sums over tokens of the accumulator are
+ *   output from colsum_acc, colsum_xq, rowsum_w, act_step/act_zero and step_w/zero_w (group = 0:
+ *   [N], one per output channel; group = -1: [1], per tensor) as exact integers, count = T.  colsum_acc = NULL: the sums over tokens of the accumulator are
  *   formed from the weight codes instead (codes = the 8-bit per-row / per-tensor codes in the
  *   K-panel layout, bits = 8, group <= 0): sum_t acc[t,n] = sum_k wq[n,k] colsum_xq[k], the same
  *   integers, so the correction can be calibrated without running the forward.
@@ -243,7 +265,7 @@ int aweq_bias_correct(int mode, const void* W_hat, aweq_dtype dt, int64_t N, int
                       const void* codes, int bits, int group,
                       const float* step_w, const int32_t* zero_w,
                       const float* bias_in, float* delta, float* bias_out, int enable_bc,
-                      void* ws, size_t ws_bytes, uint32_t* status, void* stream);
+                      uint32_t* status, void* stream);
 
 /* ---- Weight-only forward (Sec. 4.2, Table 1: INT4 / INT3 weights, FP16 activations):
  * y[t,n] = sum_k x_hat[t,k] w~[n,k] + bias[n], w~ = Step (u - Z) the de-quantised weight of Eq. 1.
@@ -260,16 +282,6 @@ int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t ldx,
                     const float* step_w, const int32_t* zero_w, int64_t N,
                     const float* bias, void* out, aweq_dtype out_dt, int64_t ldo,
                     void* ws, size_t ws_bytes, uint32_t* status, void* stream);
-
-/* ---- Diagnostic (not a stage of the method; for measurement reports).  One workgroup of four
- * wavefronts per compute unit issues iters x 16 back-to-back independent int8 32x32x32 MFMAs with
- * operand registers holding constant bytes (operand_mode 0), uniformly random bytes (1) or small
- * signed codes (2), and no memory traffic; operand_mode 3: the same loop with the binary16
- * 32x32x16 MFMA (32768 flop each) on activation- and weight-like binary16 values.  out[3] (device, uint64): shader-clock cycles of one
- * wavefront's loop, 100 MHz reference ticks of the same interval, a checksum.  The sustained
- * shader clock under matrix load is out[0] / out[1] x 100 MHz; the MFMA rate is
- * CUs x 4 x 16 x iters x 65536 ops over out[1] x 10 ns. */
-int aweq_probe_mfma_clock(int iters, int operand_mode, uint64_t* out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -180,6 +180,17 @@ void orc_scales(const float* r_x, const float* r_w, int64_t K, int enable_awe,
     if (status) *status |= st;
 }
 
+/* The per-channel quantity of the difficulty definition the method replaces (Sec. 1 and Sec. 3.2:
+ * "maximum absolute values of activations and weights"): m_i = max_t |x[t,i]| = max(|min_i|, |max_i|).
+ * orc_scales applied to (m^X, m^W) instead of (r^X, r^W) gives that variant's scale in Eq. 10's form. */
+void orc_channel_absmax(const float* cmin, const float* cmax, int64_t K, float* m)
+{
+    for (int64_t k = 0; k < K; ++k) {
+        float a = fabsf(cmin[k]), b = fabsf(cmax[k]);
+        m[k] = a > b ? a : b;
+    }
+}
+
 /* Eq. 3, weight side: W_hat = diag(s) W, i.e. W_hat[n,k] = W[n,k] * s[k]; the product is
  * one binary32 multiply, then rounded (to nearest even) to the layer's storage type. */
 void orc_fold_weight(const void* W, int dt, int64_t N, int64_t K, int64_t ldw,

@@ -116,6 +116,14 @@ def scales(r_x, r_w, enable_awe=True):
     return s, inv_s, int(st.value)
 
 
+def channel_absmax(cmin, cmax):
+    """-> m[K] = max(|cmin|, |cmax|): the abs-max difficulty variant's channel quantity."""
+    cmin, cmax = _c(cmin, np.float32), _c(cmax, np.float32)
+    m = np.empty(cmin.size, np.float32)
+    lib().orc_channel_absmax(_p(cmin), _p(cmax), i64(cmin.size), _p(m))
+    return m
+
+
 def fold_weight(W, s):
     W = _c(W)
     N, K = W.shape

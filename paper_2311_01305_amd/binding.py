@@ -13,12 +13,13 @@ _LIB_PATH = os.path.join(_HERE, "libaweq.so")
 _lib = None
 
 AWEQ_F32, AWEQ_F16, AWEQ_I8 = 0, 1, 2
-OP_CALIB_STATS, OP_EQUALIZE, OP_QUANT_WEIGHT, OP_W8A8_GEMM, OP_BIAS_CORRECT, OP_WONLY_GEMM = 0, 1, 2, 3, 4, 5
+OP_CALIB_STATS, OP_EQUALIZE, OP_QUANT_WEIGHT, OP_W8A8_GEMM, OP_BIAS_CORRECT, OP_WONLY_GEMM, OP_QUANT_ACT = 0, 1, 2, 3, 4, 5, 6
 BIAS_W8A8, BIAS_WEIGHT_ONLY = 0, 1
+SCALE_NONE, SCALE_RANGE, SCALE_ABSMAX = 0, 1, 2
 ST_DEGENERATE, ST_NONFINITE, ST_BIGQUOT, ST_SCALEGUARD, ST_ZEROPOINT = 1, 2, 4, 8, 16
 
 EXPORTS = ("aweq_workspace_size", "aweq_status_string", "aweq_calib_stats", "aweq_equalize",
-           "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct", "aweq_probe_mfma_clock",
+           "aweq_quant_weight", "aweq_quant_act", "aweq_w8a8_gemm", "aweq_bias_correct",
            "aweq_panel_bytes", "aweq_pack_panels_i8", "aweq_unpack_panels_i8", "aweq_wonly_gemm", "aweq_fold_quant_weight", "aweq_w8a8_gemm_fused",
            "aweq_calib_stats_static")
 STATIC_SCRATCH_BYTES = 16 << 20
@@ -56,28 +57,26 @@ def load_library():
     lib.aweq_calib_stats_static.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp,
                                             _vp, _vp]
     lib.aweq_equalize.restype = _i32
-    lib.aweq_equalize.argtypes = [_vp, _vp, _vp, _u64, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _i32, _i64, _i64,
+    lib.aweq_equalize.argtypes = [_vp, _vp, _vp, _u64, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _i32, _i64, _i64, _i64,
                                   _vp, _vp, _vp, _vp, _vp, _vp, _vp]
     lib.aweq_quant_weight.restype = _i32
     lib.aweq_quant_weight.argtypes = [_vp, _i32, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp]
     lib.aweq_quant_act.restype = _i32
-    lib.aweq_quant_act.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+    lib.aweq_quant_act.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp]
     lib.aweq_w8a8_gemm.restype = _i32
-    lib.aweq_w8a8_gemm.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp,
+    lib.aweq_w8a8_gemm.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _vp, _i32,
                                    _vp, _vp, _vp, _vp, _i32, _i64, _vp, _vp, _sz, _vp, _vp]
     lib.aweq_w8a8_gemm_fused.restype = _i32
     lib.aweq_w8a8_gemm_fused.argtypes = [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i64, _vp,
                                          _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp]
     lib.aweq_bias_correct.restype = _i32
     lib.aweq_bias_correct.argtypes = [_i32, _vp, _i32, _i64, _i64, _i64, _vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp,
-                                      _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _vp]
-    lib.aweq_probe_mfma_clock.restype = _i32
-    lib.aweq_probe_mfma_clock.argtypes = [_i32, _i32, _vp, _vp]
+                                      _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp]
     lib.aweq_wonly_gemm.restype = _i32
     lib.aweq_wonly_gemm.argtypes = [_vp, _i64, _i64, _i64, _vp, _i32, _i32, _vp, _vp, _i64, _vp, _vp, _i32, _i64, _vp, _sz,
                                     _vp, _vp]
     lib.aweq_fold_quant_weight.restype = _i32
-    lib.aweq_fold_quant_weight.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]
+    lib.aweq_fold_quant_weight.argtypes = [_vp, _i32, _i64, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _vp]
     lib.aweq_panel_bytes.restype = _sz
     lib.aweq_panel_bytes.argtypes = [_i64, _i64]
     lib.aweq_pack_panels_i8.restype = _i32
@@ -137,11 +136,11 @@ def aweq_calib_stats_static(M, dt, rows, K, ld, cmin, cmax, csum, count, accumul
         _ptr(r), _ptr(R), _ptr(p), _ptr(status), _stream(stream)))
 
 
-def aweq_equalize(xmin, xmax, xsum, count, wmin, wmax, K, enable_awe, s, inv_s, W, W_hat, dt, N, ldw,
+def aweq_equalize(xmin, xmax, xsum, count, wmin, wmax, K, enable_awe, s, inv_s, W, W_hat, dt, N, ldw, ldwh,
                   prev_scale, xhat_range, mu_xhat, act_step, act_zero, status=None, stream=None):
     _check(load_library().aweq_equalize(
         _ptr(xmin), _ptr(xmax), _ptr(xsum), int(count), _ptr(wmin), _ptr(wmax), K, int(enable_awe), _ptr(s),
-        _ptr(inv_s), _ptr(W), _ptr(W_hat), dt, N, ldw, _ptr(prev_scale), _ptr(xhat_range), _ptr(mu_xhat),
+        _ptr(inv_s), _ptr(W), _ptr(W_hat), dt, N, ldw, ldwh, _ptr(prev_scale), _ptr(xhat_range), _ptr(mu_xhat),
         _ptr(act_step), _ptr(act_zero), _ptr(status), _stream(stream)))
 
 
@@ -152,34 +151,30 @@ def aweq_quant_weight(W_hat, dt, N, K, ldw, bits, group, codes, step, zero, rows
         _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes, _ptr(status), _stream(stream)))
 
 
-def aweq_quant_act(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, status=None, stream=None):
+def aweq_quant_act(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, ws=None, status=None, stream=None,
+                   ws_bytes=None):
     _check(load_library().aweq_quant_act(
         _ptr(X), dt, T, K, ldx, _ptr(inv_s), _ptr(act_step), _ptr(act_zero), _ptr(xq), _ptr(rowsum_x),
-        _ptr(colsum_xq), _ptr(status), _stream(stream)))
+        _ptr(colsum_xq), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes, _ptr(status), _stream(stream)))
 
 
-def aweq_w8a8_gemm(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, wq, N, step_w, zero_w,
+def aweq_w8a8_gemm(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, wq, N, step_w, zero_w, w_group,
                    rowsum_w, bias, out_i32, out_deq, out_dt, ldo, colsum_acc, ws=None, status=None, stream=None,
                    ws_bytes=None):
     _check(load_library().aweq_w8a8_gemm(
         _ptr(X), x_dt, T, K, ldx, _ptr(inv_s), _ptr(act_step), _ptr(act_zero), _ptr(xq), _ptr(rowsum_x),
-        _ptr(colsum_xq), _ptr(wq), N, _ptr(step_w), _ptr(zero_w), _ptr(rowsum_w), _ptr(bias), _ptr(out_i32),
+        _ptr(colsum_xq), _ptr(wq), N, _ptr(step_w), _ptr(zero_w), int(w_group), _ptr(rowsum_w), _ptr(bias), _ptr(out_i32),
         _ptr(out_deq), out_dt, ldo, _ptr(colsum_acc), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
         _ptr(status), _stream(stream)))
 
 
 def aweq_bias_correct(mode, W_hat, dt, N, K, ldw, mu_xhat, count, colsum_acc, colsum_xq, rowsum_w, act_step,
-                      act_zero, codes, bits, group, step_w, zero_w, bias_in, delta, bias_out, enable_bc, ws=None,
-                      status=None, stream=None, ws_bytes=None):
+                      act_zero, codes, bits, group, step_w, zero_w, bias_in, delta, bias_out, enable_bc,
+                      status=None, stream=None):
     _check(load_library().aweq_bias_correct(
         int(mode), _ptr(W_hat), dt, N, K, ldw, _ptr(mu_xhat), int(count), _ptr(colsum_acc), _ptr(colsum_xq),
         _ptr(rowsum_w), _ptr(act_step), _ptr(act_zero), _ptr(codes), int(bits), int(group), _ptr(step_w),
-        _ptr(zero_w), _ptr(bias_in), _ptr(delta), _ptr(bias_out), int(enable_bc), _ptr(ws),
-        _nbytes(ws) if ws_bytes is None else ws_bytes, _ptr(status), _stream(stream)))
-
-
-def aweq_probe_mfma_clock(iters, operand_mode, out, stream=None):
-    _check(load_library().aweq_probe_mfma_clock(int(iters), int(operand_mode), _ptr(out), _stream(stream)))
+        _ptr(zero_w), _ptr(bias_in), _ptr(delta), _ptr(bias_out), int(enable_bc), _ptr(status), _stream(stream)))
 
 
 def aweq_panel_bytes(rows, K):
@@ -214,6 +209,6 @@ def aweq_wonly_gemm(X_hat, T, K, ldx, codes, bits, group, step_w, zero_w, N, bia
                                           _stream(stream)))
 
 
-def aweq_fold_quant_weight(W, dt, N, K, ldw, s, W_hat, bits, codes, step, zero, rowsum_w, status=None, stream=None):
-    _check(load_library().aweq_fold_quant_weight(_ptr(W), dt, N, K, ldw, _ptr(s), _ptr(W_hat), int(bits), _ptr(codes),
+def aweq_fold_quant_weight(W, dt, N, K, ldw, s, W_hat, ldwh, bits, codes, step, zero, rowsum_w, status=None, stream=None):
+    _check(load_library().aweq_fold_quant_weight(_ptr(W), dt, N, K, ldw, _ptr(s), _ptr(W_hat), ldwh, int(bits), _ptr(codes),
                                                  _ptr(step), _ptr(zero), _ptr(rowsum_w), _ptr(status), _stream(stream)))

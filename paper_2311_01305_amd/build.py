@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libaweq.so")
-SOURCES = ["api.hip", "stats.hip", "equalize.hip", "quant_weight.hip", "quant_act.hip", "gemm_i8.hip", "gemm_wonly.hip", "bias.hip", "probe.hip"]
+SOURCES = ["api.hip", "stats.hip", "equalize.hip", "quant_weight.hip", "quant_act.hip", "gemm_i8.hip", "gemm_wonly.hip", "bias.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-I", INCLUDE, "-I", CSRC]

@@ -3,6 +3,7 @@
 
 namespace aweq {
 size_t stats_ws_bytes_export(int64_t rows, int64_t K);
+size_t quant_act_ws_bytes(int64_t T, int64_t K);
 }
 
 extern "C" size_t aweq_workspace_size(aweq_op op, int64_t rows, int64_t K, int64_t N)
@@ -12,7 +13,13 @@ extern "C" size_t aweq_workspace_size(aweq_op op, int64_t rows, int64_t K, int64
     case AWEQ_OP_CALIB_STATS: return aweq::stats_ws_bytes_export(rows, K);
     case AWEQ_OP_QUANT_WEIGHT: return 16;  // tensor-wide extremes for group = -1
     case AWEQ_OP_WONLY_GEMM: return N > 0 ? (size_t)N * (size_t)K * 2 : 0;  // the binary16 weight
-    case AWEQ_OP_W8A8_GEMM: return N > 0 ? (size_t)N * 16 : 0;  // aweq_w8a8_gemm_fused: keys and sums of the output statistics
+    case AWEQ_OP_QUANT_ACT: return aweq::quant_act_ws_bytes(rows, K);  // per-slice column sums, per-chunk row sums
+    case AWEQ_OP_W8A8_GEMM: {
+        // stage 4a's partial sums (aweq_w8a8_gemm on float input), or the keys and sums of the output
+        // statistics (aweq_w8a8_gemm_fused): the larger of the two serves both
+        const size_t qa = aweq::quant_act_ws_bytes(rows, K), fs = N > 0 ? (size_t)N * 16 : 0;
+        return qa > fs ? qa : fs;
+    }
     case AWEQ_OP_EQUALIZE:
     case AWEQ_OP_BIAS_CORRECT:
     default: return 0;

@@ -40,7 +40,8 @@ __global__ __launch_bounds__(kBiasBlock) void bias_w8a8_kernel(
     const long long* __restrict__ colsum_acc, const long long* __restrict__ colsum_xq,
     const int32_t* __restrict__ rowsum_w, const float* __restrict__ act_step, const int32_t* __restrict__ act_zero,
     const float* __restrict__ step_w, const int32_t* __restrict__ zero_w, const float* __restrict__ bias_in,
-    float* __restrict__ delta, float* __restrict__ bias_out, int enable_bc, const int8_t* __restrict__ wq)
+    float* __restrict__ delta, float* __restrict__ bias_out, int enable_bc, const int8_t* __restrict__ wq,
+    int w_per_tensor)
 {
     __shared__ double slot_d[kBiasBlock / kWave];
     __shared__ long long slot_l[kBiasBlock / kWave];
@@ -78,9 +79,10 @@ __global__ __launch_bounds__(kBiasBlock) void bias_w8a8_kernel(
     if (threadIdx.x == 0) {
         const long long T = (long long)count;
         const long long zx = (long long)*act_zero - 128;
-        const long long zw = (long long)zero_w[n] - 128;
+        const int64_t pi = w_per_tensor ? 0 : n;   // one (Step, Z) for the tensor, or one per output channel
+        const long long zw = (long long)zero_w[pi] - 128;
         const long long a = (wq ? ca : colsum_acc[n]) - T * zx * (long long)rowsum_w[n] - zw * tot + T * K * zx * zw;
-        const double yq = (double)*act_step * (double)step_w[n] * (double)a / (double)T;
+        const double yq = (double)*act_step * (double)step_w[pi] * (double)a / (double)T;
         const double d = acc - yq;
         delta[n] = (float)d;
         bias_out[n] = (float)((bias_in ? (double)bias_in[n] : 0.0) + (enable_bc ? d : 0.0));
@@ -157,9 +159,9 @@ extern "C" int aweq_bias_correct(int mode, const void* W_hat, aweq_dtype dt, int
                                  const void* codes, int bits, int group,
                                  const float* step_w, const int32_t* zero_w,
                                  const float* bias_in, float* delta, float* bias_out, int enable_bc,
-                                 void* ws, size_t ws_bytes, uint32_t* status, void* stream)
+                                 uint32_t* status, void* stream)
 {
-    (void)ws; (void)ws_bytes; (void)status;
+    (void)status;   // this stage meets no numeric condition it would have to report
     if (!W_hat || !mu_xhat || !step_w || !zero_w || !delta || !bias_out) return AWEQ_ERR_NULL;
     if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
     if (N <= 0 || N > 0x7fffffffll || K <= 0 || ldw < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
@@ -173,15 +175,17 @@ extern "C" int aweq_bias_correct(int mode, const void* W_hat, aweq_dtype dt, int
         // without the GEMM's column sums they are formed from the 8-bit per-row / per-tensor codes (K-panel layout)
         const int8_t* wq = colsum_acc ? nullptr : reinterpret_cast<const int8_t*>(codes);
         if (wq && (bits != 8 || group > 0)) return AWEQ_ERR_BITS;
+        if (group != 0 && group != -1) return AWEQ_ERR_GROUP;   // the int8 path has one scale per output channel or per tensor
+        const int pt = group == -1;
         if (wq && !aligned16(wq)) return AWEQ_ERR_ALIGN;
         const long long* ca = reinterpret_cast<const long long*>(colsum_acc);
         const long long* cx = reinterpret_cast<const long long*>(colsum_xq);
         if (f16)
             bias_w8a8_kernel<true><<<(unsigned)N, kBiasBlock, 0, st>>>(W_hat, K, ldw, mu_xhat, count, ca, cx, rowsum_w, act_step,
-                                                                     act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc, wq);
+                                                                     act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc, wq, pt);
         else
             bias_w8a8_kernel<false><<<(unsigned)N, kBiasBlock, 0, st>>>(W_hat, K, ldw, mu_xhat, count, ca, cx, rowsum_w, act_step,
-                                                                      act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc, wq);
+                                                                      act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc, wq, pt);
     } else if (mode == AWEQ_BIAS_WEIGHT_ONLY) {
         if (!codes) return AWEQ_ERR_NULL;
         if (bits != 8 && bits != 4 && bits != 3) return AWEQ_ERR_BITS;

@@ -16,8 +16,10 @@ __global__ __launch_bounds__(1024) void equalize_scales(
     uint32_t st = 0;
     float lo = INFINITY, hi = -INFINITY;
     for (int64_t k = threadIdx.x; k < K; k += blockDim.x) {
-        const float r_x = xmax[k] - xmin[k];
-        const float r_w = wmax[k] - wmin[k];
+        // the per-channel quantity the scale balances: the channel range (Eq. 10), or - the definition the
+        // method replaces (Sec. 1, Sec. 3.2: maximum absolute values) - the channel's largest magnitude
+        const float r_x = enable_awe == AWEQ_SCALE_ABSMAX ? fmaxf(fabsf(xmin[k]), fabsf(xmax[k])) : xmax[k] - xmin[k];
+        const float r_w = enable_awe == AWEQ_SCALE_ABSMAX ? fmaxf(fabsf(wmin[k]), fabsf(wmax[k])) : wmax[k] - wmin[k];
         float sk = 1.0f;
         if (enable_awe) {
             if (!(r_x >= 1e-5f) || !(r_w >= 1e-5f)) {
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(1024) void equalize_scales(
 // down the rows of their slice, so s stays in registers.
 template <bool F16>
 __global__ __launch_bounds__(256) void fold_weight(const void* __restrict__ Wv, void* __restrict__ Ov,
-                                                   int64_t N, int64_t K, int64_t ldw,
+                                                   int64_t N, int64_t K, int64_t ldw, int64_t ldwh,
                                                    const float* __restrict__ s, int64_t rows_per_block)
 {
     constexpr int E = F16 ? 8 : 4;
@@ -81,14 +83,14 @@ __global__ __launch_bounds__(256) void fold_weight(const void* __restrict__ Wv, 
                 f.y = rounded_f32(f.y * sc[2 * i + 1]);
                 o.h[i] = f16x2{(_Float16)f.x, (_Float16)f.y};
             }
-            *reinterpret_cast<Half8*>(O + n * ldw + col) = o;
+            *reinterpret_cast<Half8*>(O + n * ldwh + col) = o;
         } else {
             const float* W = reinterpret_cast<const float*>(Wv);
             float* O = reinterpret_cast<float*>(Ov);
             Float4 v = *reinterpret_cast<const Float4*>(W + n * ldw + col);
 #pragma unroll
             for (int i = 0; i < 4; ++i) v.f[i] = v.f[i] * sc[i];
-            *reinterpret_cast<Float4*>(O + n * ldw + col) = v;
+            *reinterpret_cast<Float4*>(O + n * ldwh + col) = v;
         }
     }
 }
@@ -100,7 +102,7 @@ using namespace aweq;
 extern "C" int aweq_equalize(const float* xmin, const float* xmax, const double* xsum, uint64_t count,
                              const float* wmin, const float* wmax, int64_t K, int enable_awe,
                              float* s, float* inv_s,
-                             const void* W, void* W_hat, aweq_dtype dt, int64_t N, int64_t ldw,
+                             const void* W, void* W_hat, aweq_dtype dt, int64_t N, int64_t ldw, int64_t ldwh,
                              float* prev_scale, float* xhat_range, float* mu_xhat,
                              float* act_step, int32_t* act_zero,
                              uint32_t* status, void* stream)
@@ -109,12 +111,15 @@ extern "C" int aweq_equalize(const float* xmin, const float* xmax, const double*
     if (mu_xhat && !xsum) return AWEQ_ERR_NULL;
     if ((act_step == nullptr) != (act_zero == nullptr)) return AWEQ_ERR_NULL;
     if (K <= 0 || (K % 8) != 0) return AWEQ_ERR_SHAPE;
+    if (enable_awe < 0 || enable_awe > AWEQ_SCALE_ABSMAX) return AWEQ_ERR_SHAPE;
     if (mu_xhat && count == 0) return AWEQ_ERR_SHAPE;
     if (W) {
         if (!W_hat) return AWEQ_ERR_NULL;
         if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
-        if (N <= 0 || ldw < K) return AWEQ_ERR_SHAPE;
-        if (!aligned16(W) || !aligned16(W_hat) || ((size_t)ldw * dtype_size(dt)) % 16 != 0) return AWEQ_ERR_ALIGN;
+        if (N <= 0 || ldw < K || ldwh < K) return AWEQ_ERR_SHAPE;
+        if (!aligned16(W) || !aligned16(W_hat) || ((size_t)ldw * dtype_size(dt)) % 16 != 0 ||
+            ((size_t)ldwh * dtype_size(dt)) % 16 != 0)
+            return AWEQ_ERR_ALIGN;
     }
     hipStream_t st = as_stream(stream);
     equalize_scales<<<1, 1024, 0, st>>>(xmin, xmax, xsum, count, wmin, wmax, K, enable_awe, s, inv_s, prev_scale,
@@ -127,9 +132,9 @@ extern "C" int aweq_equalize(const float* xmin, const float* xmax, const double*
         const int64_t rpb = cdiv(N, slices);
         dim3 grid(gx, (unsigned)cdiv(N, rpb));
         if (dt == AWEQ_F16)
-            fold_weight<true><<<grid, 256, 0, st>>>(W, W_hat, N, K, ldw, s, rpb);
+            fold_weight<true><<<grid, 256, 0, st>>>(W, W_hat, N, K, ldw, ldwh, s, rpb);
         else
-            fold_weight<false><<<grid, 256, 0, st>>>(W, W_hat, N, K, ldw, s, rpb);
+            fold_weight<false><<<grid, 256, 0, st>>>(W, W_hat, N, K, ldw, ldwh, s, rpb);
     }
     return launch_status();
 }

@@ -25,7 +25,11 @@
 // Workgroups are numbered so that the ones resident on one XCD (which share an L2) form a
 // compact patch of the output.
 #include "common.hpp"
+#include <atomic>
+#include <mutex>
+#include <set>
 #include <type_traits>
+#include <utility>
 
 namespace aweq {
 
@@ -63,6 +67,7 @@ struct GemmArgs {
     const int32_t* rowsum_x;
     const int32_t* rowsum_w;
     const float* bias;
+    int w_per_tensor;  // step_w / zero_w hold one entry for the whole weight instead of one per output channel
     int tiles_m, tiles_n, patch_m, patch_n, patches_n, n_patches;
     int n_ids;  // workgroup ids that may name a tile (whole rounds of patches over the XCDs)
     // fused epilogues on the de-quantised binary16 output y (the next layer's calibration input)
@@ -222,9 +227,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_i8_generic(GemmArgs g)
         for (int j = 0; j < 4; ++j) {
             const int64_t n = col_base + j * 32;
             if (n >= g.N) continue;
-            const int zw = g.zero_w[n] - 128;
+            const int64_t pi = g.w_per_tensor ? 0 : n;
+            const int zw = g.zero_w[pi] - 128;
             if (zw < -128 || zw > 127 || zx < -128 || zx > 127) raise_status(g.status, AWEQ_ST_ZEROPOINT);
-            const double scale = sx * (double)g.step_w[n];
+            const double scale = sx * (double)g.step_w[pi];
             const double bs = g.bias ? (double)g.bias[n] : 0.0;
             // integer part in wrap-around 32-bit arithmetic: the final value fits (|.| <= 255^2 K)
             const unsigned cn = (unsigned)Ki * (unsigned)zx * (unsigned)zw - (unsigned)zx * (unsigned)g.rowsum_w[n];
@@ -530,8 +536,16 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                 rsx[hh] = t < g.T ? g.rowsum_x[t] : 0;
             }
             if (n_ok) {
-                sw = *reinterpret_cast<const Float4*>(g.step_w + n);
-                const v4i zw4 = *reinterpret_cast<const v4i*>(g.zero_w + n);
+                v4i zw4;
+                if (g.w_per_tensor) {
+                    const float s0 = g.step_w[0];
+                    const int z0 = g.zero_w[0];
+                    sw = Float4{{s0, s0, s0, s0}};
+                    zw4 = v4i{z0, z0, z0, z0};
+                } else {
+                    sw = *reinterpret_cast<const Float4*>(g.step_w + n);
+                    zw4 = *reinterpret_cast<const v4i*>(g.zero_w + n);
+                }
                 const v4i rw4 = *reinterpret_cast<const v4i*>(g.rowsum_w + n);
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
@@ -595,11 +609,10 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         char* slab = lds + 3 * kSlot + wave * 8192;
         const int wr_t = lane & 31;
         const int wr_sw = wr_t & 15, wr_half = lane >> 5;           // chunk (8 j + 2 q + l / 32) ^ (t & 15)
+        // column sums of the accumulator itself (never of the corrected integer, which wraps for zero points far
+        // outside [0, 255]: the sums the bias correction needs do not depend on zero points)
         long long csum[4] = {0, 0, 0, 0};
-        // with a de-quantised output the column sums come from the corrected integers that are converted
-        // anyway (exact in fp64: 32 values below 2^31): sum acc = sum iv - rows cn + Z'w sum rowsum_x
-        double dsum[4] = {0.0, 0.0, 0.0, 0.0};
-        int rs_sum = 0, rows_in = 0;
+        int rows_in = 0;   // rows of this lane inside T (the fused code epilogue turns unsigned sums into signed ones)
         float ymn[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, ymx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
         double ysum[4] = {0.0, 0.0, 0.0, 0.0};   // exact: at most 128 binary16 values each
         float cqf[4] = {0.f, 0.f, 0.f, 0.f};     // column sums of the next layer's unsigned codes over this tile (exact: 32 rows)
@@ -641,9 +654,8 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                             const double bd = EPI == 3 ? (double)bs.f[c] : bsd[c];
                             if constexpr (DEQ == 1) y[c] = (float)(div * scale[c] + bd);
                             else y[c] = (float)__builtin_fma(div, scale[c], bd);
-                            if constexpr (COLSUM) dsum[c] += div;
                         }
-                        if constexpr (COLSUM) { rs_sum += (int)rs; ++rows_in; }
+                        if constexpr ((EPI & 2) != 0) ++rows_in;
                         if constexpr (DEQ == 2) {
                             typedef _Float16 h4 __attribute__((ext_vector_type(4)));
                             if constexpr (EPI != 0) {
@@ -697,7 +709,7 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
                             __builtin_nontemporal_store(of, reinterpret_cast<f4*>(reinterpret_cast<float*>(g.out_deq) + t * g.ldo + n));
                         }
                     }
-                    if constexpr (COLSUM && DEQ == 0) {
+                    if constexpr (COLSUM) {
 #pragma unroll
                         for (int c = 0; c < 4; ++c) csum[c] += o[c];
                     }
@@ -737,7 +749,7 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
             int cq[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                cq[c] = (int)cqf[c] - 128 * rows_in;   // (the fused variants always carry the column sums: rows_in is counted)
+                cq[c] = (int)cqf[c] - 128 * rows_in;
                 cq[c] += partner<4>(cq[c]);
                 cq[c] += partner<5>(cq[c]);
             }
@@ -749,11 +761,6 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_fast(GemmArgs g)
         }
         if constexpr (EPI != 0 || DEQ != 0) raise_status(g.status, est);
         if constexpr (COLSUM) {
-            if constexpr (DEQ != 0) {
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    csum[c] = (long long)dsum[c] - (long long)rows_in * (long long)(int)cn[c] + (long long)zwv[c] * (long long)rs_sum;
-            }
             // lanes l, l ^ 16, l ^ 32 hold the same channels for different tokens
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -789,7 +796,8 @@ __global__ void zero_fill_u32_gemm(uint32_t* p, int64_t n)
 // from quant_act.hip
 int launch_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx, const float* inv_s,
                      const float* act_step, const int32_t* act_zero, int8_t* xq, int32_t* rowsum_x,
-                     int64_t* colsum_xq, uint32_t* status, hipStream_t st);
+                     int64_t* colsum_xq, void* ws, uint32_t* status, hipStream_t st);
+int check_quant_act_ws(int64_t T, int64_t K, const int32_t* rowsum_x, const int64_t* colsum_xq, const void* ws, size_t ws_bytes);
 int check_quant_act_args(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx, const float* inv_s,
                          const float* act_step, const int32_t* act_zero, const int8_t* xq, bool xq_optional);
 
@@ -824,13 +832,37 @@ static int plan_gemm(GemmArgs& g, int64_t T, int64_t N, int64_t K, int64_t& bloc
 
 // persistent launch of a fast-kernel instantiation: one workgroup per compute unit (a multiple of
 // 8, so that id % 8 stays the XCD)
+// compute units of the current device, asked once per device
+static int device_cus(int& dev, int& cus)
+{
+    constexpr int kMaxDev = 64;
+    static std::atomic<int> cached[kMaxDev];
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return AWEQ_ERR_LAUNCH;
+    cus = cached[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return AWEQ_ERR_LAUNCH;
+        cached[dev].store(cus, std::memory_order_relaxed);
+    }
+    return AWEQ_OK;
+}
+
+// the dynamic LDS limit of a kernel is raised once per (kernel, device), not per launch
+static int raise_lds_limit(const void* fn, int dev, int bytes)
+{
+    static std::mutex mu;
+    static std::set<std::pair<const void*, int>> done;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({fn, dev})) return AWEQ_OK;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return AWEQ_ERR_LAUNCH;
+    done.insert({fn, dev});
+    return AWEQ_OK;
+}
+
 static int launch_fast(const void* fn, GemmArgs& g, int64_t blocks, hipStream_t st)
 {
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, fast::kLds) != hipSuccess) return AWEQ_ERR_LAUNCH;
-    void* args[] = {&g};
     int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-        return AWEQ_ERR_LAUNCH;
+    if (device_cus(dev, cus) != AWEQ_OK || raise_lds_limit(fn, dev, fast::kLds) != AWEQ_OK) return AWEQ_ERR_LAUNCH;
+    void* args[] = {&g};
     int64_t grid = (cus / kXcds) * kXcds;
     if (grid < kXcds) grid = kXcds;
     if (grid > blocks) grid = blocks;
@@ -840,6 +872,7 @@ static int launch_fast(const void* fn, GemmArgs& g, int64_t blocks, hipStream_t 
 
 static void clear_fused(GemmArgs& g)
 {
+    g.w_per_tensor = 0;
     g.act = 0; g.ykeys = nullptr; g.yfix = nullptr; g.next_inv_s = nullptr; g.next_step = nullptr; g.next_zero = nullptr;
     g.yq = nullptr; g.rowsum_y = nullptr; g.colsum_yq = nullptr; g.status = nullptr;
 }
@@ -882,14 +915,14 @@ using namespace aweq;
 extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t K, int64_t ldx,
                               const float* inv_s, const float* act_step, const int32_t* act_zero,
                               int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
-                              const int8_t* wq, int64_t N, const float* step_w, const int32_t* zero_w,
+                              const int8_t* wq, int64_t N, const float* step_w, const int32_t* zero_w, int w_group,
                               const int32_t* rowsum_w, const float* bias,
                               int32_t* out_i32, void* out_deq, aweq_dtype out_dt, int64_t ldo,
                               int64_t* colsum_acc, void* ws, size_t ws_bytes,
                               uint32_t* status, void* stream)
 {
-    (void)ws; (void)ws_bytes;
     if (!X || !wq) return AWEQ_ERR_NULL;
+    if (w_group != 0 && w_group != -1) return AWEQ_ERR_GROUP;
     if (x_dt != AWEQ_F32 && x_dt != AWEQ_F16 && x_dt != AWEQ_I8) return AWEQ_ERR_DTYPE;
     if (T <= 0 || N <= 0 || K <= 0 || (K % 8) != 0) return AWEQ_ERR_SHAPE;
     if (K > 32768) return AWEQ_ERR_SHAPE;  // keeps 128*128*K and 255*255*K inside int32
@@ -898,7 +931,9 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
         if (ldx != K) return AWEQ_ERR_SHAPE;
         a = reinterpret_cast<const int8_t*>(X);
     } else {
-        const int rc = check_quant_act_args(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq, false);
+        int rc = check_quant_act_args(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq, false);
+        if (rc != AWEQ_OK) return rc;
+        rc = check_quant_act_ws(T, K, rowsum_x, colsum_xq, ws, ws_bytes);
         if (rc != AWEQ_OK) return rc;
         a = xq;
     }
@@ -912,7 +947,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     }
     hipStream_t st = as_stream(stream);
     if (x_dt != AWEQ_I8) {
-        const int rc = launch_quant_act(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, status, st);
+        const int rc = launch_quant_act(X, x_dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, ws, status, st);
         if (rc != AWEQ_OK) return rc;
     }
     if (!out_i32 && !out_deq && !colsum_acc) return launch_status();
@@ -924,6 +959,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     g.act_step = act_step; g.act_zero = act_zero; g.step_w = step_w; g.zero_w = zero_w;
     g.rowsum_x = rowsum_x; g.rowsum_w = rowsum_w; g.bias = bias;
     clear_fused(g);
+    g.w_per_tensor = w_group == -1;
     g.status = status;
     int64_t blocks = 0;
     const int prc = plan_gemm(g, T, N, K, blocks);
@@ -934,7 +970,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
     // the fast kernel stores 16-byte output quads
     bool fast_ok = (N % 4) == 0;
     if (out_i32 && (!aligned16(out_i32) || (ldo % 4) != 0)) fast_ok = false;
-    if (out_deq && (!aligned16(out_deq) || (ldo % 4) != 0 || !aligned16(step_w) || !aligned16(zero_w) ||
+    if (out_deq && (!aligned16(out_deq) || (ldo % 4) != 0 || (w_group == 0 && (!aligned16(step_w) || !aligned16(zero_w))) ||
                     !aligned16(rowsum_w) || (bias && !aligned16(bias))))
         fast_ok = false;
     if (fast_ok) {
@@ -948,8 +984,8 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
         return launch_fast(fn, g, blocks, st);
     }
     const size_t lds_bytes = 2 * 2 * kTileBytes;  // 64 KiB
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_i8_generic), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds_bytes) != hipSuccess)
+    int dev = 0, cus = 0;
+    if (device_cus(dev, cus) != AWEQ_OK || raise_lds_limit(reinterpret_cast<const void*>(gemm_i8_generic), dev, (int)lds_bytes) != AWEQ_OK)
         return AWEQ_ERR_LAUNCH;
     gemm_i8_generic<<<(unsigned)blocks, kGemmThreads, lds_bytes, st>>>(g);
     return launch_status();

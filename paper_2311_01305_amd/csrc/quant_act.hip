@@ -158,10 +158,9 @@ template <bool F16>
 __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     const void* __restrict__ X, int64_t T, int64_t K, int64_t ldx, const float* __restrict__ inv_s,
     const float* __restrict__ act_step, const int32_t* __restrict__ act_zero, int8_t* __restrict__ xq,
-    int32_t* __restrict__ rowsum_x, long long* __restrict__ colsum_xq, int rows_per_block, int chunks,
+    int32_t* __restrict__ rowsum_x, int32_t* __restrict__ colsum_part, int rows_per_block, int chunks,
     uint32_t* status)
 {
-    const int multi_chunk = chunks > 1;
     const int chunk = (int)(blockIdx.x % (unsigned)chunks);
     const int64_t slice = blockIdx.x / (unsigned)chunks;
     __shared__ int lds_rs[kQaMaxRows][kQaWaves];
@@ -255,59 +254,118 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
     if (big >= 16777216.0f) st |= AWEQ_ST_BIGQUOT;
     raise_status(status, st);
 
-    if (colsum_xq) {
-        // lanes l, l ^ 8, l ^ 16, l ^ 32 hold the same columns for different rows
+    if (colsum_part) {
+        // lanes l, l ^ 8, l ^ 16, l ^ 32 hold the same columns for different rows; this block's sums over
+        // its row slice (at most 512 rows of codes in [-128, 127]) go to row `slice` of the partial buffer
+        int32_t* const part = colsum_part + slice * K;
 #pragma unroll
-        for (int j = 0; j < kQaVpt; ++j)
+        for (int j = 0; j < kQaVpt; ++j) {
+            int v[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                int v = fast ? ((int)csf[j][i] - 128 * my_rows) : csi[j][i];
-                v += xor8(v);
-                v += partner<4>(v);
-                v += partner<5>(v);
-                if (lane < 8 && valid[j])
-                    atomicAdd(reinterpret_cast<unsigned long long*>(&colsum_xq[col0 + j * kPanel + i]), (unsigned long long)(long long)v);
+                v[i] = fast ? ((int)csf[j][i] - 128 * my_rows) : csi[j][i];
+                v[i] += xor8(v[i]);
+                v[i] += partner<4>(v[i]);
+                v[i] += partner<5>(v[i]);
             }
+            if (lane < 8 && valid[j]) {
+                typedef int v4i_ __attribute__((ext_vector_type(4)));
+                v4i_* d = reinterpret_cast<v4i_*>(part + col0 + j * kPanel);
+                d[0] = v4i_{v[0], v[1], v[2], v[3]};
+                d[1] = v4i_{v[4], v[5], v[6], v[7]};
+            }
+        }
     }
     __syncthreads();
+    // with several column chunks `rowsum_x` is the partial buffer [chunks][T], folded by the merge kernel
     if (rowsum_x)
         for (int i = threadIdx.x; i < nrows; i += kQaBlock) {
             int tot = 0;
 #pragma unroll
             for (int w = 0; w < kQaWaves; ++w) tot += lds_rs[i][w];
-            if (multi_chunk) atomicAdd(&rowsum_x[r0 + i], tot);
-            else rowsum_x[r0 + i] = tot;
+            rowsum_x[(int64_t)chunk * T + r0 + i] = tot;
         }
 }
 
-__global__ void zero_fill_u32(uint32_t* p, int64_t n)
+// Fold the per-slice column sums (fixed order, 64-bit) and the per-chunk row sums.  Blocks
+// [0, col_blocks) own 32 columns each: 8 groups of 32 threads take every 8th slice and meet in LDS;
+// the remaining blocks own 256 rows each.
+constexpr int kQaMergeCols = 32, kQaMergeParts = 8;
+__global__ __launch_bounds__(kQaMergeCols * kQaMergeParts) void quant_act_merge(
+    const int32_t* __restrict__ colsum_part, int slices, int64_t K, long long* __restrict__ colsum_xq,
+    const int32_t* __restrict__ rowsum_part, int chunks, int64_t T, int32_t* __restrict__ rowsum_x, int col_blocks)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
+    if ((int)blockIdx.x < col_blocks) {
+        __shared__ long long s_s[kQaMergeParts][kQaMergeCols];
+        const int c = threadIdx.x & (kQaMergeCols - 1), part = threadIdx.x / kQaMergeCols;
+        const int64_t k = (int64_t)blockIdx.x * kQaMergeCols + c;
+        long long s = 0;
+        if (k < K)
+            for (int j = part; j < slices; j += kQaMergeParts) s += colsum_part[(int64_t)j * K + k];
+        s_s[part][c] = s;
+        __syncthreads();
+        if (part != 0 || k >= K) return;
+#pragma unroll
+        for (int q = 1; q < kQaMergeParts; ++q) s += s_s[q][c];
+        colsum_xq[k] = s;
+    } else {
+        const int64_t t = ((int64_t)blockIdx.x - col_blocks) * (kQaMergeCols * kQaMergeParts) + threadIdx.x;
+        if (t >= T) return;
+        int tot = 0;
+        for (int c = 0; c < chunks; ++c) tot += rowsum_part[(int64_t)c * T + t];
+        rowsum_x[t] = tot;
+    }
+}
+
+struct QaPlan {
+    int chunks;      // column chunks of 8 panels
+    int64_t slices;  // row slices
+    int64_t rpb;     // rows per slice
+};
+
+static QaPlan qa_plan(int64_t T, int64_t K)
+{
+    QaPlan p;
+    p.chunks = (int)cdiv(panel_count(K), kQaPanels);
+    int64_t slices = cdiv(8192, p.chunks);
+    int64_t rpb = cdiv(T, slices);
+    rpb = cdiv(rpb, kQaRowsPerIter) * kQaRowsPerIter;
+    if (rpb > kQaMaxRows) rpb = kQaMaxRows;
+    p.rpb = rpb;
+    p.slices = cdiv(T, rpb);
+    return p;
+}
+
+// workspace: per-slice column sums [slices][K] int32, then (several column chunks only) per-chunk
+// row sums [chunks][T] int32
+size_t quant_act_ws_bytes(int64_t T, int64_t K)
+{
+    const QaPlan p = qa_plan(T, K);
+    return (size_t)p.slices * (size_t)K * 4 + (p.chunks > 1 ? (size_t)p.chunks * (size_t)T * 4 : 0);
 }
 
 int launch_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx, const float* inv_s,
                      const float* act_step, const int32_t* act_zero, int8_t* xq, int32_t* rowsum_x,
-                     int64_t* colsum_xq, uint32_t* status, hipStream_t st)
+                     int64_t* colsum_xq, void* ws, uint32_t* status, hipStream_t st)
 {
-    const int chunks = (int)cdiv(panel_count(K), kQaPanels);
-    int64_t slices = cdiv(8192, chunks);
-    int64_t rpb = cdiv(T, slices);
-    rpb = cdiv(rpb, kQaRowsPerIter) * kQaRowsPerIter;
-    if (rpb > kQaMaxRows) rpb = kQaMaxRows;
-    slices = cdiv(T, rpb);
-    if (slices * chunks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
-    const int multi = chunks > 1;
-    // the accumulating outputs start from zero (a fill kernel, so the call can be graph-captured)
-    if (colsum_xq) zero_fill_u32<<<(unsigned)cdiv(2 * K, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(colsum_xq), 2 * K);
-    if (rowsum_x && multi) zero_fill_u32<<<(unsigned)cdiv(T, 256), 256, 0, st>>>(reinterpret_cast<uint32_t*>(rowsum_x), T);
-    const unsigned grid = (unsigned)(slices * chunks);
+    const QaPlan p = qa_plan(T, K);
+    if (p.slices * p.chunks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+    const bool multi = p.chunks > 1;
+    int32_t* const colsum_part = colsum_xq ? reinterpret_cast<int32_t*>(ws) : nullptr;
+    int32_t* const rowsum_part = reinterpret_cast<int32_t*>(ws) + (size_t)p.slices * K;
+    int32_t* const rs_out = !rowsum_x ? nullptr : (multi ? rowsum_part : rowsum_x);
+    const unsigned grid = (unsigned)(p.slices * p.chunks);
     if (dt == AWEQ_F16)
-        quant_act_kernel<true><<<grid, kQaBlock, 0, st>>>(X, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x,
-                                                          reinterpret_cast<long long*>(colsum_xq), (int)rpb, chunks, status);
+        quant_act_kernel<true><<<grid, kQaBlock, 0, st>>>(X, T, K, ldx, inv_s, act_step, act_zero, xq, rs_out, colsum_part,
+                                                          (int)p.rpb, p.chunks, status);
     else
-        quant_act_kernel<false><<<grid, kQaBlock, 0, st>>>(X, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x,
-                                                           reinterpret_cast<long long*>(colsum_xq), (int)rpb, chunks, status);
+        quant_act_kernel<false><<<grid, kQaBlock, 0, st>>>(X, T, K, ldx, inv_s, act_step, act_zero, xq, rs_out, colsum_part,
+                                                           (int)p.rpb, p.chunks, status);
+    const int col_blocks = colsum_xq ? (int)cdiv(K, kQaMergeCols) : 0;
+    const int64_t row_blocks = (rowsum_x && multi) ? cdiv(T, kQaMergeCols * kQaMergeParts) : 0;
+    if (col_blocks + row_blocks > 0)
+        quant_act_merge<<<(unsigned)(col_blocks + row_blocks), kQaMergeCols * kQaMergeParts, 0, st>>>(
+            colsum_part, (int)p.slices, K, reinterpret_cast<long long*>(colsum_xq), rowsum_part, p.chunks, T, rowsum_x, col_blocks);
     return launch_status();
 }
 
@@ -321,6 +379,16 @@ int check_quant_act_args(const void* X, aweq_dtype dt, int64_t T, int64_t K, int
     return AWEQ_OK;
 }
 
+// the sums need the workspace (rowsum_x only with several column chunks)
+int check_quant_act_ws(int64_t T, int64_t K, const int32_t* rowsum_x, const int64_t* colsum_xq, const void* ws, size_t ws_bytes)
+{
+    const bool need = colsum_xq || (rowsum_x && qa_plan(T, K).chunks > 1);
+    if (!need) return AWEQ_OK;
+    if (!ws || ws_bytes < quant_act_ws_bytes(T, K)) return AWEQ_ERR_WORKSPACE;
+    if (!aligned16(ws)) return AWEQ_ERR_ALIGN;
+    return AWEQ_OK;
+}
+
 }  // namespace aweq
 
 using namespace aweq;
@@ -328,10 +396,12 @@ using namespace aweq;
 extern "C" int aweq_quant_act(const void* X, aweq_dtype dt, int64_t T, int64_t K, int64_t ldx,
                               const float* inv_s, const float* act_step, const int32_t* act_zero,
                               int8_t* xq, int32_t* rowsum_x, int64_t* colsum_xq,
-                              uint32_t* status, void* stream)
+                              void* ws, size_t ws_bytes, uint32_t* status, void* stream)
 {
     if (!xq && !rowsum_x && !colsum_xq) return AWEQ_ERR_NULL;   // nothing to produce
-    const int rc = check_quant_act_args(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, true);
+    int rc = check_quant_act_args(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, true);
     if (rc != AWEQ_OK) return rc;
-    return launch_quant_act(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, status, as_stream(stream));
+    rc = check_quant_act_ws(T, K, rowsum_x, colsum_xq, ws, ws_bytes);
+    if (rc != AWEQ_OK) return rc;
+    return launch_quant_act(X, dt, T, K, ldx, inv_s, act_step, act_zero, xq, rowsum_x, colsum_xq, ws, status, as_stream(stream));
 }

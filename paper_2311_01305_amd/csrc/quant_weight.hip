@@ -361,21 +361,22 @@ extern "C" int aweq_quant_weight(const void* W_hat, aweq_dtype dt, int64_t N, in
 // Fold and quantise in one pass over W (per-row quantizer): what aweq_equalize's fold followed by
 // aweq_quant_weight with group = 0 produce, with W read once and W_hat not read back.
 extern "C" int aweq_fold_quant_weight(const void* W, aweq_dtype dt, int64_t N, int64_t K, int64_t ldw,
-                                      const float* s, void* W_hat, int bits, void* codes, float* step,
+                                      const float* s, void* W_hat, int64_t ldwh, int bits, void* codes, float* step,
                                       int32_t* zero, int32_t* rowsum_w, uint32_t* status, void* stream)
 {
     if (!W || !s || !W_hat || !codes || !step || !zero) return AWEQ_ERR_NULL;
     if (dt != AWEQ_F32 && dt != AWEQ_F16) return AWEQ_ERR_DTYPE;
     if (bits != 8 && bits != 4 && bits != 3) return AWEQ_ERR_BITS;
-    if (N <= 0 || N > 0x7fffffffll || K <= 0 || ldw < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
+    if (N <= 0 || N > 0x7fffffffll || K <= 0 || ldw < K || ldwh < K || (K % 8) != 0) return AWEQ_ERR_SHAPE;
     if (K > (int64_t)kQwBlock * 8 * kQwMaxUnits) return AWEQ_ERR_SHAPE;  // a row must fit the block's registers
     if (bits == 3 && (K % 32) != 0) return AWEQ_ERR_ALIGN;
     if (bits != 8 && rowsum_w) return AWEQ_ERR_BITS;
-    if (!aligned16(W) || !aligned16(W_hat) || !aligned16(s) || ((size_t)ldw * dtype_size(dt)) % 16 != 0 || !aligned16(codes))
+    if (!aligned16(W) || !aligned16(W_hat) || !aligned16(s) || ((size_t)ldw * dtype_size(dt)) % 16 != 0 ||
+        ((size_t)ldwh * dtype_size(dt)) % 16 != 0 || !aligned16(codes))
         return AWEQ_ERR_ALIGN;
     hipStream_t st = as_stream(stream);
     uint8_t* cb = reinterpret_cast<uint8_t*>(codes);
-#define AWEQ_FQ(F, B) quant_weight_row<F, B, false, true><<<(unsigned)N, kQwBlock, 0, st>>>(W, K, ldw, cb, step, zero, rowsum_w, status, s, W_hat, ldw)
+#define AWEQ_FQ(F, B) quant_weight_row<F, B, false, true><<<(unsigned)N, kQwBlock, 0, st>>>(W, K, ldw, cb, step, zero, rowsum_w, status, s, W_hat, ldwh)
     if (dt == AWEQ_F16) { if (bits == 8) AWEQ_FQ(true, 8); else if (bits == 4) AWEQ_FQ(true, 4); else AWEQ_FQ(true, 3); }
     else { if (bits == 8) AWEQ_FQ(false, 8); else if (bits == 4) AWEQ_FQ(false, 4); else AWEQ_FQ(false, 3); }
 #undef AWEQ_FQ

@@ -41,16 +41,30 @@ inline size_t stats_ws_bytes(int64_t rows, int64_t K)
     // sized for the narrower lane width (more chunks never increases the slice count)
     StatsPlan a = stats_plan(rows, K, 8), b = stats_plan(rows, K, 4);
     int s = a.slices > b.slices ? a.slices : b.slices;
-    return (size_t)s * (size_t)K * (sizeof(float) * 2 + sizeof(double));
+    // partial rows, then the control words of the merge kernel (a ticket and the keys of the tensor's extremes)
+    return (size_t)s * (size_t)K * (sizeof(float) * 2 + sizeof(double)) + 16;
+}
+
+// order-preserving unsigned key of a float (and back): integer atomics then find extremes
+__device__ __forceinline__ uint32_t stats_key(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float stats_key_float(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
 // ---- binary16: 8 columns per lane
 __global__ __launch_bounds__(kStatsBlock) void col_stats_partial_f16(
     const _Float16* __restrict__ M, int64_t rows, int64_t K, int64_t ld, int64_t rows_per_slice,
-    float* __restrict__ pmin, float* __restrict__ pmax, double* __restrict__ psum)
+    float* __restrict__ pmin, float* __restrict__ pmax, double* __restrict__ psum, uint32_t* __restrict__ ctl)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
+    // the merge kernel that follows on the stream starts from a zero ticket and identity keys
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { ctl[0] = 0u; ctl[1] = 0xffffffffu; ctl[2] = 0u; }
     const int64_t col = ((int64_t)blockIdx.x * kWave + lane) * 8;
     const bool active = col < K;
     const int64_t r_begin = (int64_t)blockIdx.y * rows_per_slice;
@@ -133,10 +147,11 @@ __global__ __launch_bounds__(kStatsBlock) void col_stats_partial_f16(
 // ---- binary32: 4 columns per lane, every element added in fp64
 __global__ __launch_bounds__(kStatsBlock) void col_stats_partial_f32(
     const float* __restrict__ M, int64_t rows, int64_t K, int64_t ld, int64_t rows_per_slice,
-    float* __restrict__ pmin, float* __restrict__ pmax, double* __restrict__ psum)
+    float* __restrict__ pmin, float* __restrict__ pmax, double* __restrict__ psum, uint32_t* __restrict__ ctl)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { ctl[0] = 0u; ctl[1] = 0xffffffffu; ctl[2] = 0u; }
     const int64_t col = ((int64_t)blockIdx.x * kWave + lane) * 4;
     const bool active = col < K;
     const int64_t r_begin = (int64_t)blockIdx.y * rows_per_slice;
@@ -203,14 +218,19 @@ __global__ __launch_bounds__(kStatsBlock) void col_stats_partial_f32(
 // Fold the row slices and merge with what the caller already holds.  A block owns 32 columns;
 // its 8 groups of 32 threads take every 8th slice each and meet in LDS in a fixed order, so
 // the fp64 sums are reproducible.
+// finalize: r = max - min per channel, R = tensor max - tensor min, p = r / R (Eq. 4) need every
+// block's columns, so each block adds its extremes to two keys and takes a ticket; the block that
+// draws the last ticket finds all columns merged and writes r, R, p.
 constexpr int kMergeCols = 32, kMergeParts = 8;
 __global__ __launch_bounds__(kMergeCols * kMergeParts) void col_stats_merge(
     const float* __restrict__ pmin, const float* __restrict__ pmax, const double* __restrict__ psum,
-    int slices, int64_t K, int64_t rows, float* __restrict__ cmin, float* __restrict__ cmax,
-    double* __restrict__ csum, uint64_t* __restrict__ count, int accumulate, uint32_t* status)
+    int slices, int64_t K, int64_t rows, float* cmin, float* cmax,
+    double* __restrict__ csum, uint64_t* __restrict__ count, int accumulate, uint32_t* status,
+    int finalize, float* __restrict__ r, float* __restrict__ R, float* __restrict__ p, uint32_t* ctl)
 {
     __shared__ float s_a[kMergeParts][kMergeCols], s_b[kMergeParts][kMergeCols];
     __shared__ double s_s[kMergeParts][kMergeCols];
+    __shared__ int s_last;
     const int c = threadIdx.x & (kMergeCols - 1), part = threadIdx.x / kMergeCols;
     const int64_t k = (int64_t)blockIdx.x * kMergeCols + c;
     if (blockIdx.x == 0 && threadIdx.x == 0 && count) *count = (accumulate ? *count : 0ull) + (uint64_t)rows;
@@ -224,44 +244,47 @@ __global__ __launch_bounds__(kMergeCols * kMergeParts) void col_stats_merge(
         }
     s_a[part][c] = a; s_b[part][c] = b; s_s[part][c] = s;
     __syncthreads();
-    if (part != 0 || k >= K) return;
+    if (part == 0 && k < K) {
 #pragma unroll
-    for (int q = 1; q < kMergeParts; ++q) {
-        a = fminf(a, s_a[q][c]);
-        b = fmaxf(b, s_b[q][c]);
-        s += s_s[q][c];
+        for (int q = 1; q < kMergeParts; ++q) {
+            a = fminf(a, s_a[q][c]);
+            b = fmaxf(b, s_b[q][c]);
+            s += s_s[q][c];
+        }
+        // a non-finite input makes the fp64 sum (Inf / NaN) or an extreme (Inf) non-finite
+        if (!isfinite(s) || isinf(a) || isinf(b)) raise_status(status, AWEQ_ST_NONFINITE);
+        if (accumulate) {
+            a = fminf(a, cmin[k]);
+            b = fmaxf(b, cmax[k]);
+            if (csum) s += csum[k];
+        }
+        cmin[k] = a;
+        cmax[k] = b;
+        if (csum) csum[k] = s;
     }
-    // a non-finite input makes the fp64 sum (Inf / NaN) or an extreme (Inf) non-finite
-    if (!isfinite(s) || isinf(a) || isinf(b)) raise_status(status, AWEQ_ST_NONFINITE);
-    if (accumulate) {
-        a = fminf(a, cmin[k]);
-        b = fmaxf(b, cmax[k]);
-        if (csum) s += csum[k];
+    if (!finalize) return;
+    if (part == 0) {
+        // this block's extremes (lanes past K hold the identities) -> the tensor's keys
+        a = group_allreduce<5>(k < K ? a : INFINITY, OpMin());
+        b = group_allreduce<5>(k < K ? b : -INFINITY, OpMax());
+        if (c == 0) {
+            atomicMin(&ctl[1], stats_key(a));
+            atomicMax(&ctl[2], stats_key(b));
+            __threadfence();   // columns and keys are visible device-wide before the ticket is
+            s_last = atomicAdd(&ctl[0], 1u) == gridDim.x - 1;
+        }
     }
-    cmin[k] = a;
-    cmax[k] = b;
-    if (csum) csum[k] = s;
-}
-
-// r = max - min per channel, R = tensor max - tensor min, p = r / R  (Eq. 4).  One block.
-__global__ __launch_bounds__(1024) void col_stats_finalize(
-    const float* __restrict__ cmin, const float* __restrict__ cmax, int64_t K,
-    float* __restrict__ r, float* __restrict__ R, float* __restrict__ p)
-{
-    __shared__ float slot[16];
-    float a = INFINITY, b = -INFINITY;
-    for (int64_t k = threadIdx.x; k < K; k += blockDim.x) {
-        a = fminf(a, cmin[k]);
-        b = fmaxf(b, cmax[k]);
-    }
-    a = block_allreduce<16>(a, OpMin(), slot);
-    b = block_allreduce<16>(b, OpMax(), slot);
-    const float RR = b - a;
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();           // every other block's columns and keys are visible to this one
+    const float RR = stats_key_float(__hip_atomic_load(&ctl[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) -
+                     stats_key_float(__hip_atomic_load(&ctl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     if (threadIdx.x == 0) *R = RR;
-    for (int64_t k = threadIdx.x; k < K; k += blockDim.x) {
-        const float rk = cmax[k] - cmin[k];
-        r[k] = rk;
-        if (p) p[k] = rk / RR;
+    for (int64_t kk = threadIdx.x; kk < K; kk += blockDim.x) {
+        const float rk = __hip_atomic_load(&cmax[kk], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+                         __hip_atomic_load(&cmin[kk], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        r[kk] = rk;
+        if (p) p[kk] = rk / RR;
     }
 }
 
@@ -279,16 +302,16 @@ static int run_calib_stats(const void* M, aweq_dtype dt, int64_t rows, int64_t K
     double* psum = reinterpret_cast<double*>(ws);
     float* pmin = reinterpret_cast<float*>(psum + (size_t)plan.slices * K);
     float* pmax = pmin + (size_t)plan.slices * K;
+    uint32_t* ctl = reinterpret_cast<uint32_t*>(pmax + (size_t)plan.slices * K);
     dim3 grid(plan.col_chunks, plan.slices);
     if (dt == AWEQ_F16)
         col_stats_partial_f16<<<grid, kStatsBlock, 0, st>>>(reinterpret_cast<const _Float16*>(M), rows, K, ld,
-                                                             plan.rows_per_slice, pmin, pmax, psum);
+                                                             plan.rows_per_slice, pmin, pmax, psum, ctl);
     else
         col_stats_partial_f32<<<grid, kStatsBlock, 0, st>>>(reinterpret_cast<const float*>(M), rows, K, ld,
-                                                             plan.rows_per_slice, pmin, pmax, psum);
-    col_stats_merge<<<(unsigned)cdiv(K, kMergeCols), kMergeCols * kMergeParts, 0, st>>>(pmin, pmax, psum, plan.slices, K, rows, cmin, cmax,
-                                                            csum, count, accumulate, status);
-    if (finalize) col_stats_finalize<<<1, 1024, 0, st>>>(cmin, cmax, K, r, R, p);
+                                                             plan.rows_per_slice, pmin, pmax, psum, ctl);
+    col_stats_merge<<<(unsigned)cdiv(K, kMergeCols), kMergeCols * kMergeParts, 0, st>>>(
+        pmin, pmax, psum, plan.slices, K, rows, cmin, cmax, csum, count, accumulate, status, finalize, r, R, p, ctl);
     return launch_status();
 }
 
@@ -355,7 +378,8 @@ extern "C" int aweq_calib_stats_static(const void* M, aweq_dtype dt, int64_t row
     void* ptr = nullptr;
     const int src = static_scratch(&ptr);
     if (src != AWEQ_OK) return src;
-    // every partial row the merge reads is written by this call's first kernel: nothing to clear
+    // every partial row the merge reads, and the merge's ticket and keys, are written by this call's first
+    // kernel: the array's contents from earlier calls never matter and nothing has to be cleared
     return run_calib_stats(M, dt, rows, K, ld, cmin, cmax, csum, count, accumulate, finalize, r, R, p, ptr, status,
                            as_stream(stream));
 }

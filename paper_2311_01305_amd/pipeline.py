@@ -51,8 +51,6 @@ class LayerBuffers:
         t["status"] = torch.zeros(1, dtype=i32, device=d)
         t["W_hat"] = e(N, K, dtype=self.dtype)
         ng = 1 if self.group < 0 else (N if self.group == 0 else N * (K // self.group))
-        if self.group < 0 and self.w8a8:
-            ng = N  # the GEMM epilogue and the bias correction index (Step, Z) by output channel
         # 8-bit per-row / per-tensor codes are the GEMM operand: K-panel layout
         panel_w = self.bits == 8 and self.group <= 0
         t["codes"] = e(B.aweq_panel_bytes(N, K) if panel_w else N * K * self.bits // 8, dtype=torch.int8)
@@ -60,7 +58,8 @@ class LayerBuffers:
         t["rowsum_w"] = e(N, dtype=i32)
         t["delta"], t["bias_out"] = e(N, dtype=f32), e(N, dtype=f32)
         ws = max(B.aweq_workspace_size(B.OP_CALIB_STATS, T, K, N), B.aweq_workspace_size(B.OP_CALIB_STATS, N, K, N),
-                 B.aweq_workspace_size(B.OP_QUANT_WEIGHT, N, K, N), 16)
+                 B.aweq_workspace_size(B.OP_QUANT_WEIGHT, N, K, N),
+                 B.aweq_workspace_size(B.OP_W8A8_GEMM, T, K, N) if self.w8a8 else 0, 16)
         t["ws"] = e(ws, dtype=torch.uint8)
         if self.w8a8:
             t["xq"] = e(B.aweq_panel_bytes(T, K), dtype=torch.int8)
@@ -89,41 +88,39 @@ def calibrate_layer(X: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tenso
                        t["r_x"], t["R_x"], t["p_x"], t["ws"], st, stream)
     B.aweq_calib_stats(W, dt, N, K, W.stride(0), t["wmin"], t["wmax"], None, t["wcount"], 0, 1,
                        t["r_w"], t["R_w"], t["p_w"], t["ws"], st, stream)
-    fused = fused_weight_pass and buf.group == 0 and W.stride(0) == K
+    fused = fused_weight_pass and buf.group == 0
+    ldw, ldwh = W.stride(0), t["W_hat"].stride(0)   # W may be a pitched view (a row slice of a fused qkv weight)
     # stage 2: equalization scales, fold into W, equalised activation range / mean / quantizer
     B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, enable_awe, t["s"], t["inv_s"],
-                    None if fused else W, t["W_hat"], dt, N, W.stride(0), None, t["xhat_range"], t["mu_xhat"],
+                    None if fused else W, t["W_hat"], dt, N, ldw, ldwh, None, t["xhat_range"], t["mu_xhat"],
                     t["act_step"], t["act_zero"], st, stream)
     # stage 3: weight quantizer (fused: fold and quantise in one pass over W)
     if fused:
-        B.aweq_fold_quant_weight(W, dt, N, K, K, t["s"], t["W_hat"], buf.bits, t["codes"], t["step_w"], t["zero_w"],
+        B.aweq_fold_quant_weight(W, dt, N, K, ldw, t["s"], t["W_hat"], ldwh, buf.bits, t["codes"], t["step_w"], t["zero_w"],
                                  t["rowsum_w"] if buf.bits == 8 else None, st, stream)
     else:
-        B.aweq_quant_weight(t["W_hat"], dt, N, K, K, buf.bits, buf.group, t["codes"], t["step_w"], t["zero_w"],
+        B.aweq_quant_weight(t["W_hat"], dt, N, K, ldwh, buf.bits, buf.group, t["codes"], t["step_w"], t["zero_w"],
                             t["rowsum_w"] if (buf.bits == 8 and buf.group <= 0) else None, t["ws"], st, stream)
-    if buf.w8a8 and buf.group < 0:
-        # per-tensor weights (Sec. 3): the one (Step, Z) is repeated for every output channel (a copy)
-        t["step_w"][1:].copy_(t["step_w"][0].expand(N - 1))
-        t["zero_w"][1:].copy_(t["zero_w"][0].expand(N - 1))
+    wg = -1 if buf.group < 0 else 0   # per-tensor weights (Sec. 3): one (Step, Z), read as such by stages 4 and 5
     if buf.w8a8 and not forward:
         B.aweq_quant_act(X, dt, T, K, X.stride(0), t["inv_s"], t["act_step"], t["act_zero"], None, None, t["colsum_xq"],
-                         st, stream)
-        B.aweq_bias_correct(B.BIAS_W8A8, t["W_hat"], dt, N, K, K, t["mu_xhat"], T, None, t["colsum_xq"], t["rowsum_w"],
-                            t["act_step"], t["act_zero"], t["codes"], 8, 0, t["step_w"], t["zero_w"], bias, t["delta"],
-                            t["bias_out"], enable_bc, None, st, stream)
+                         t["ws"], st, stream)
+        B.aweq_bias_correct(B.BIAS_W8A8, t["W_hat"], dt, N, K, ldwh, t["mu_xhat"], T, None, t["colsum_xq"], t["rowsum_w"],
+                            t["act_step"], t["act_zero"], t["codes"], 8, wg, t["step_w"], t["zero_w"], bias, t["delta"],
+                            t["bias_out"], enable_bc, st, stream)
     elif buf.w8a8:
         # stage 4: activation quantizer + int8 GEMM (+ per-channel output sums for stage 5)
         B.aweq_w8a8_gemm(X, dt, T, K, X.stride(0), t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],
-                         t["colsum_xq"], t["codes"], N, t["step_w"], t["zero_w"], t["rowsum_w"], bias,
-                         t.get("out_i32"), t.get("out_deq"), dt, N, t["colsum_acc"], None, st, stream)
+                         t["colsum_xq"], t["codes"], N, t["step_w"], t["zero_w"], wg, t["rowsum_w"], bias,
+                         t.get("out_i32"), t.get("out_deq"), dt, N, t["colsum_acc"], t["ws"], st, stream)
         # stage 5: bias correction
-        B.aweq_bias_correct(B.BIAS_W8A8, t["W_hat"], dt, N, K, K, t["mu_xhat"], T, t["colsum_acc"], t["colsum_xq"],
-                            t["rowsum_w"], t["act_step"], t["act_zero"], None, 8, 0, t["step_w"], t["zero_w"], bias,
-                            t["delta"], t["bias_out"], enable_bc, None, st, stream)
+        B.aweq_bias_correct(B.BIAS_W8A8, t["W_hat"], dt, N, K, ldwh, t["mu_xhat"], T, t["colsum_acc"], t["colsum_xq"],
+                            t["rowsum_w"], t["act_step"], t["act_zero"], None, 8, wg, t["step_w"], t["zero_w"], bias,
+                            t["delta"], t["bias_out"], enable_bc, st, stream)
     else:
-        B.aweq_bias_correct(B.BIAS_WEIGHT_ONLY, t["W_hat"], dt, N, K, K, t["mu_xhat"], T, None, None, None, None, None,
+        B.aweq_bias_correct(B.BIAS_WEIGHT_ONLY, t["W_hat"], dt, N, K, ldwh, t["mu_xhat"], T, None, None, None, None, None,
                             t["codes"], buf.bits, buf.group, t["step_w"], t["zero_w"], bias, t["delta"],
-                            t["bias_out"], enable_bc, None, st, stream)
+                            t["bias_out"], enable_bc, st, stream)
     return t
 
 
@@ -158,7 +155,7 @@ class GroupBuffers:
         t["xq"] = e(B.aweq_panel_bytes(T, K), dtype=torch.int8)
         t["rowsum_x"] = e(T, dtype=i32)
         t["colsum_xq"] = e(K, dtype=i64)
-        ws = max([B.aweq_workspace_size(B.OP_CALIB_STATS, T, K, 0)] +
+        ws = max([B.aweq_workspace_size(B.OP_CALIB_STATS, T, K, 0), B.aweq_workspace_size(B.OP_QUANT_ACT, T, K, 0)] +
                  [B.aweq_workspace_size(B.OP_CALIB_STATS, N, K, N) for N in self.Ns] + [16])
         t["ws"] = e(ws, dtype=torch.uint8)
         for N in self.Ns:
@@ -186,21 +183,21 @@ def calibrate_group(X: torch.Tensor, Ws, biases, gb: GroupBuffers, enable_awe: b
         last = i == len(Ws) - 1
         B.aweq_calib_stats(W, dt, W.shape[0], K, W.stride(0), t["wmin"], t["wmax"], None, t["wcount"], int(i > 0),
                            int(last), t["r_w"], t["R_w"], t["p_w"], t["ws"], st, stream)
+    # the scales (and the activation quantizer) depend on the group's merged ranges only: computed once
+    B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, enable_awe, t["s"], t["inv_s"],
+                    None, None, dt, 0, K, K, None, t["xhat_range"], t["mu_xhat"], t["act_step"], t["act_zero"], st, stream)
     for W, p in zip(Ws, gb.per):
-        N = W.shape[0]
-        B.aweq_equalize(t["xmin"], t["xmax"], t["xsum"], T, t["wmin"], t["wmax"], K, enable_awe, t["s"], t["inv_s"],
-                        W, p["W_hat"], dt, N, W.stride(0), None, t["xhat_range"], t["mu_xhat"], t["act_step"],
-                        t["act_zero"], st, stream)
-        B.aweq_quant_weight(p["W_hat"], dt, N, K, K, 8, 0, p["codes"], p["step_w"], p["zero_w"], p["rowsum_w"],
-                            t["ws"], st, stream)
+        # fold (Eq. 3) and per-channel quantizer in one pass over each weight
+        B.aweq_fold_quant_weight(W, dt, W.shape[0], K, W.stride(0), t["s"], p["W_hat"], p["W_hat"].stride(0), 8, p["codes"],
+                                 p["step_w"], p["zero_w"], p["rowsum_w"], st, stream)
     B.aweq_quant_act(X, dt, T, K, X.stride(0), t["inv_s"], t["act_step"], t["act_zero"], t["xq"], t["rowsum_x"],
-                     t["colsum_xq"], st, stream)
+                     t["colsum_xq"], t["ws"], st, stream)
     for W, b, p in zip(Ws, biases, gb.per):
         N = W.shape[0]
         B.aweq_w8a8_gemm(t["xq"], B.AWEQ_I8, T, K, K, None, t["act_step"], t["act_zero"], None, t["rowsum_x"], None,
-                         p["codes"], N, p["step_w"], p["zero_w"], p["rowsum_w"], b, p.get("out_i32"),
+                         p["codes"], N, p["step_w"], p["zero_w"], 0, p["rowsum_w"], b, p.get("out_i32"),
                          p.get("out_deq"), dt, N, p["colsum_acc"], None, st, stream)
-        B.aweq_bias_correct(B.BIAS_W8A8, p["W_hat"], dt, N, K, K, t["mu_xhat"], T, p["colsum_acc"], t["colsum_xq"],
-                            p["rowsum_w"], t["act_step"], t["act_zero"], None, 8, 0, p["step_w"], p["zero_w"], b,
-                            p["delta"], p["bias_out"], enable_bc, None, st, stream)
+        B.aweq_bias_correct(B.BIAS_W8A8, p["W_hat"], dt, N, K, p["W_hat"].stride(0), t["mu_xhat"], T, p["colsum_acc"],
+                            t["colsum_xq"], p["rowsum_w"], t["act_step"], t["act_zero"], None, 8, 0, p["step_w"], p["zero_w"], b,
+                            p["delta"], p["bias_out"], enable_bc, st, stream)
     return gb

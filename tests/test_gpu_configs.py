@@ -133,7 +133,7 @@ def test_weight_only_layer_shapes(mods, orc, li, bits):
 
 def test_w8a8_per_tensor_weights(mods, orc):
     """The paper's own stated granularity (Sec. 3: per-tensor for weights and activations) through the
-    whole W8A8 path: one (Step, Z) for the weight, repeated per output channel for stages 4 and 5."""
+    whole W8A8 path: one (Step, Z) for the weight, read as such by stages 4 and 5 (w_group = -1)."""
     B, pipeline, synth = mods
     wl = synth.scaled(synth.WORKLOADS[3], 768, [synth.Linear("fc", 320, 512)])
     progress("W8A8 with per-tensor weight quantizer")
@@ -147,7 +147,7 @@ def test_w8a8_per_tensor_weights(mods, orc):
     q = orc.quant_weight(Wh, 8, -1)
     assert q["step"].size == 1
     sw, zw = np.full(N, q["step"].reshape(-1)[0], np.float32), np.full(N, q["zero"].reshape(-1)[0], np.int32)
-    assert np.array_equal(h(t["step_w"]), sw) and np.array_equal(h(t["zero_w"]), zw)
+    assert h(t["step_w"]).size == 1 and h(t["step_w"])[0] == sw[0] and h(t["zero_w"])[0] == zw[0]
     wq = orc.pack_codes(q["codes_u"], 8)
     assert np.array_equal(from_panels(h(t["codes"]), N, K), wq)
     a = orc.quant_act(X, gi, step, zero)
@@ -159,6 +159,69 @@ def test_w8a8_per_tensor_weights(mods, orc):
     ref = orc.w8a8_output_direct(a["xq"], wq, step, zero, sw, zw, None)
     got = h(t["out_deq"]).astype(np.float64)
     assert np.all(np.abs(got - ref) <= np.maximum(np.abs(ref), 2.0 ** -14) * 2.0 ** -10)
+
+
+def test_pitched_weight_through_the_pipeline(mods, orc):
+    """W as a row slice of a wider matrix (e.g. one third of a fused qkv weight stored [N x 3K]... or a
+    column block of it): its pitch differs from the folded weight's.  Both fold routes must read W with
+    its pitch and write W_hat with its own, and every later stage must see the right W_hat."""
+    B, pipeline, synth = mods
+    wl = synth.scaled(synth.WORKLOADS[3], 512, [synth.Linear("fc", 192, 256)])
+    progress("pitched W through calibrate_layer (both fold routes)")
+    seed, T, K, N = 555, 512, 256, 192
+    big = synth.make_weight_np(seed, N, 3 * K + 64, wl.dtype)          # pitch 832 elements
+    Wv = big[:, K + 64:2 * K + 64]                                      # the middle block: offset 320 elements (16-byte aligned)
+    W = np.ascontiguousarray(Wv)
+    X = synth.make_act_np(seed, T, K, wl)
+    big_d = dev(big)
+    W_d = big_d[:, K + 64:2 * K + 64]
+    assert W_d.stride(0) == 3 * K + 64 and not W_d.is_contiguous()
+    for fused in (False, True):
+        buf = pipeline.LayerBuffers(T, K, N, torch.float16, want_out_i32=True, device=DEV)
+        t = pipeline.calibrate_layer(dev(X), W_d, None, buf, fused_weight_pass=fused)
+        Wh, gi, lo, hi = front(orc, X, W, t)          # includes W_hat == the oracle's fold, bit for bit
+        q = orc.quant_weight(Wh, 8, 0)
+        wq = orc.pack_codes(q["codes_u"], 8)
+        assert np.array_equal(from_panels(h(t["codes"]), N, K), wq)
+        step, zero, _ = orc.qparams(lo, hi, 8)
+        a = orc.quant_act(X, gi, step, zero)
+        acc = orc.gemm_i8(a["xq"], wq)
+        assert np.array_equal(h(t["out_i32"]), acc)
+        d_ref, _ = orc.bias_w8a8(Wh, h(t["mu_xhat"]), T, acc.astype(np.int64).sum(axis=0), a["colsum_xq"], q["rowsum_w"],
+                                 step, zero, q["step"], q["zero"], None)
+        assert np.max(np.abs(h(t["delta"]) - d_ref)) <= 1e-5 * np.max(np.abs(d_ref))
+    # the matrix around the view is untouched
+    assert np.array_equal(h(big_d).view(np.uint16), big.view(np.uint16))
+
+
+def test_absmax_scale_switch(mods, orc):
+    """AWEQ_SCALE_ABSMAX: the difficulty definition the method replaces (Sec. 1: maximum absolute values)
+    in Eq. 10's form, as a switch next to the method's own channel ranges."""
+    B, pipeline, synth = mods
+    wl = synth.scaled(synth.WORKLOADS[2], 640, [synth.Linear("fc", 128, 512)])
+    progress("abs-max scale switch")
+    seed, T, K, N = 909, 640, 512, 128
+    W = synth.make_weight_np(seed, N, K, wl.dtype)
+    X = (synth.make_act_np(seed, T, K, wl).astype(np.float32) + np.float32(1.5)).astype(np.float16)   # shifted: m != r / 2
+    buf = pipeline.LayerBuffers(T, K, N, torch.float16, want_out_i32=True, device=DEV)
+    t = pipeline.calibrate_layer(dev(X), dev(W), None, buf, enable_awe=B.SCALE_ABSMAX)
+    sx, sw = orc.col_stats(X), orc.col_stats(W, want_sum=False)
+    m_x, m_w = orc.channel_absmax(sx["cmin"], sx["cmax"]), orc.channel_absmax(sw["cmin"], sw["cmax"])
+    s, inv_s, _ = orc.scales(m_x, m_w)
+    np.testing.assert_allclose(h(t["s"]), s, rtol=1e-5)
+    r_x, _, _ = orc.ranges(sx["cmin"], sx["cmax"])
+    r_w, _, _ = orc.ranges(sw["cmin"], sw["cmax"])
+    s_range, _, _ = orc.scales(r_x, r_w)
+    assert np.max(np.abs(s / s_range - 1)) > 0.05        # the two definitions really differ on this layer
+    gs, gi = h(t["s"]), h(t["inv_s"])
+    Wh = orc.fold_weight(W, gs)
+    assert np.array_equal(h(t["W_hat"]).view(np.uint16), Wh.view(np.uint16))
+    lo, hi, mu = orc.xhat_stats(sx["cmin"], sx["cmax"], sx["csum"], sx["count"], gi)
+    step, zero, _ = orc.qparams(lo, hi, 8)
+    assert h(t["act_step"])[0] == step and int(h(t["act_zero"])[0]) == zero
+    q = orc.quant_weight(Wh, 8, 0)
+    a = orc.quant_act(X, gi, step, zero)
+    assert np.array_equal(h(t["out_i32"]), orc.gemm_i8(a["xq"], orc.pack_codes(q["codes_u"], 8)))
 
 
 def test_ablation_switches(mods, orc):

@@ -77,7 +77,7 @@ def unfused(B, c, d):
     T, K, N = c["T"], c["K"], c["N"]
     y = torch.zeros((T, N), dtype=torch.float16, device=DEV)
     cs = e(N, dtype=torch.int64)
-    B.aweq_w8a8_gemm(d.xq, B.AWEQ_I8, T, K, K, None, d.step_x, d.zero_x, None, d.rowsum_x, None, d.wq, N, d.step_w, d.zero_w,
+    B.aweq_w8a8_gemm(d.xq, B.AWEQ_I8, T, K, K, None, d.step_x, d.zero_x, None, d.rowsum_x, None, d.wq, N, d.step_w, d.zero_w, 0,
                      d.rowsum_w, d.bias, None, y, B.AWEQ_F16, N, cs, None, None)
     return host(y), host(cs)
 

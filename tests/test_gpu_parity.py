@@ -41,6 +41,12 @@ def e(*shape, dtype):
     return torch.empty(shape, dtype=dtype, device=DEV)
 
 
+def qa_ws(B, T, K):
+    """Workspace of the activation quantizer, filled with garbage: its contents must not matter."""
+    n = max(16, B.aweq_workspace_size(B.OP_QUANT_ACT, T, K))
+    return torch.full((n,), 0x5A, dtype=torch.uint8, device=DEV)
+
+
 def progress(msg):
     print(f"[gpu-parity] {msg}", flush=True)
 
@@ -143,7 +149,7 @@ def gpu_equalize(B, sx, sw, W, enable_awe=True, prev_scale=None):
     rng_t, step, zero = e(2, dtype=torch.float32), e(1, dtype=torch.float32), e(1, dtype=torch.int32)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     B.aweq_equalize(dev(sx["cmin"]), dev(sx["cmax"]), dev(sx["csum"]), sx["count"], dev(sw["cmin"]), dev(sw["cmax"]),
-                    K, int(enable_awe), s, inv_s, W_t, W_hat, dtc(B, W), N, K, prev_scale, rng_t, mu, step, zero, status)
+                    K, int(enable_awe), s, inv_s, W_t, W_hat, dtc(B, W), N, K, K, prev_scale, rng_t, mu, step, zero, status)
     return dict(s=s, inv_s=inv_s, W_hat=W_hat, xhat_range=rng_t, mu_xhat=mu, act_step=step, act_zero=zero, status=status)
 
 
@@ -273,7 +279,7 @@ def test_fold_quant_weight_equals_two_calls(B, orc, dtype, N, K, bits):
     rowsum = e(N, dtype=torch.int32) if bits == 8 else None
     W_hat = torch.zeros((N, K), dtype=torch.float16 if dtype == np.float16 else torch.float32, device=DEV)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
-    B.aweq_fold_quant_weight(dev(W), dtc(B, W), N, K, K, dev(s), W_hat, bits, codes, step, zero, rowsum, status)
+    B.aweq_fold_quant_weight(dev(W), dtc(B, W), N, K, K, dev(s), W_hat, K, bits, codes, step, zero, rowsum, status)
     assert np.array_equal(host(W_hat).view(np.uint8), Wh.view(np.uint8))
     assert np.array_equal(host(step), o["step"]) and np.array_equal(host(zero), o["zero"])
     got = host(codes)
@@ -284,7 +290,7 @@ def test_fold_quant_weight_equals_two_calls(B, orc, dtype, N, K, bits):
     assert int(host(status)[0]) == o["status"]
     # in place: W_hat aliasing W
     Wd = dev(W)
-    B.aweq_fold_quant_weight(Wd, dtc(B, W), N, K, K, dev(s), Wd, bits, codes, step, zero, rowsum, status)
+    B.aweq_fold_quant_weight(Wd, dtc(B, W), N, K, K, dev(s), Wd, K, bits, codes, step, zero, rowsum, status)
     assert np.array_equal(host(Wd).view(np.uint8), Wh.view(np.uint8)) and np.array_equal(host(zero), o["zero"])
 
 
@@ -327,7 +333,7 @@ def test_fold_rounds_twice_at_the_row_extremes(B, orc):
     step, zero, rowsum = e(N, dtype=torch.float32), e(N, dtype=torch.int32), e(N, dtype=torch.int32)
     W_hat = torch.zeros((N, K), dtype=torch.float16, device=DEV)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
-    B.aweq_fold_quant_weight(dev(W), B.AWEQ_F16, N, K, K, dev(s), W_hat, 8, codes, step, zero, rowsum, status)
+    B.aweq_fold_quant_weight(dev(W), B.AWEQ_F16, N, K, K, dev(s), W_hat, K, 8, codes, step, zero, rowsum, status)
     assert np.array_equal(host(W_hat).view(np.uint16), Wh.view(np.uint16))
     assert np.array_equal(host(step), o["step"]) and np.array_equal(host(zero), o["zero"])
     assert np.array_equal(from_panels(host(codes), N, K).reshape(-1), orc.pack_codes(o["codes_u"], 8).view(np.uint8).reshape(-1))
@@ -343,7 +349,7 @@ def gpu_quant_act(B, X, inv_s, step, zero):
     rs, cs = e(T, dtype=torch.int32), e(K, dtype=torch.int64)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     B.aweq_quant_act(dev(X), dtc(B, X), T, K, K, dev(inv_s), dev(np.array([step], np.float32)),
-                     dev(np.array([zero], np.int32)), xq, rs, cs, status)
+                     dev(np.array([zero], np.int32)), xq, rs, cs, qa_ws(B, T, K), status)
     return dict(xq=xq, rowsum_x=rs, colsum_xq=cs, status=status)
 
 
@@ -469,7 +475,7 @@ def gpu_gemm(B, xq, wq, want_i32=True, deq=None, colsum=True):
                      dev(np.array([deq["zero_x"]], np.int32)) if deq else None,
                      None, dev(deq["rowsum_x"]) if deq else None, None, dev(to_panels(wq)), N,
                      dev(deq["step_w"]) if deq else None, dev(deq["zero_w"]) if deq else None,
-                     dev(deq["rowsum_w"]) if deq else None, dev(deq["bias"]) if deq and deq["bias"] is not None else None,
+                     int(deq.get("w_group", 0)) if deq else 0, dev(deq["rowsum_w"]) if deq else None, dev(deq["bias"]) if deq and deq["bias"] is not None else None,
                      out, out_deq, out_dt, N, cs, None, status)
     return out, out_deq, cs
 
@@ -575,7 +581,7 @@ def test_gemm_dequant_zero_points_outside_the_code_range(B, orc, N):
         status = torch.zeros(1, dtype=torch.int32, device=DEV)
         B.aweq_w8a8_gemm(dev(to_panels(xq)), B.AWEQ_I8, T_, K_, K_, None, dev(np.array([deq["step_x"]], np.float32)),
                          dev(np.array([deq["zero_x"]], np.int32)), None, dev(deq["rowsum_x"]), None, dev(to_panels(wq)), N,
-                         dev(deq["step_w"]), dev(deq["zero_w"]), dev(deq["rowsum_w"]), dev(deq["bias"]), None, out_deq,
+                         dev(deq["step_w"]), dev(deq["zero_w"]), 0, dev(deq["rowsum_w"]), dev(deq["bias"]), None, out_deq,
                          B.AWEQ_F16 if odt == np.float16 else B.AWEQ_F32, N, cs, None, status)
         got = host(out_deq)
         if odt == np.float32:
@@ -584,6 +590,53 @@ def test_gemm_dequant_zero_points_outside_the_code_range(B, orc, N):
             assert np.all(np.abs(got.astype(np.float64) - ref) <= np.maximum(np.abs(ref), 2.0 ** -14) * 2.0 ** -10)
         assert np.array_equal(host(cs), orc.gemm_i8(xq, wq).astype(np.int64).sum(axis=0))
         assert int(host(status)[0]) == B.ST_ZEROPOINT
+
+
+def test_gemm_column_sums_do_not_depend_on_zero_points(B, orc):
+    """colsum_acc is the sum of the accumulator itself.  With an all-positive weight row, a large
+    contraction and a zero point far outside [0, 255] the corrected integer of the de-quantisation no
+    longer fits 32 bits (the status bit says so); the column sums must still be exact, and equal with
+    and without a de-quantised output, in the tiled and in the generic kernel."""
+    progress("gemm column sums under wrapping zero points")
+    rng = np.random.default_rng(99)
+    T, K = 300, 8192
+    for N in (260, 262):
+        xq = rng.integers(-128, 128, (T, K), dtype=np.int8)
+        wq = rng.integers(-128, 128, (N, K), dtype=np.int8)
+        wq[3] = 127
+        xq[:8] = 127
+        zero_w = rng.integers(100, 160, N).astype(np.int32)
+        zero_w[3], zero_w[7] = 128 - 4000000, 128 + 3000000      # |Z'w rowsum_x| up to 4e6 * 127 * 8192 >> 2^31
+        deq = dict(dtype=np.float32, step_x=0.01, zero_x=133, step_w=rng.uniform(1e-4, 1e-3, N).astype(np.float32),
+                   zero_w=zero_w, bias=None, rowsum_x=xq.astype(np.int64).sum(axis=1).astype(np.int32),
+                   rowsum_w=wq.astype(np.int64).sum(axis=1).astype(np.int32))
+        ref = orc.gemm_i8(xq, wq).astype(np.int64).sum(axis=0)
+        for odt in (np.float32, np.float16):
+            deq["dtype"] = odt
+            _, _, cs_deq = gpu_gemm(B, xq, wq, want_i32=False, deq=deq)
+            assert np.array_equal(host(cs_deq), ref), (N, odt)
+        _, _, cs_plain = gpu_gemm(B, xq, wq, want_i32=False)
+        assert np.array_equal(host(cs_plain), ref)
+
+
+def test_gemm_dequant_per_tensor_weight_scale(B, orc):
+    """w_group = -1: one (Step, Z) for the whole weight (the paper's per-tensor setting, Sec. 3), read from
+    index 0 by the epilogue; equal to the per-channel call with that pair repeated."""
+    progress("gemm dequant epilogue, per-tensor weight scale")
+    rng = np.random.default_rng(17)
+    T, K = 300, 320
+    for N in (260, 262):
+        xq = rng.integers(-128, 128, (T, K), dtype=np.int8)
+        wq = rng.integers(-128, 128, (N, K), dtype=np.int8)
+        common = dict(dtype=np.float32, step_x=0.0123, zero_x=141, bias=rng.standard_normal(N).astype(np.float32),
+                      rowsum_x=xq.astype(np.int64).sum(axis=1).astype(np.int32), rowsum_w=wq.astype(np.int64).sum(axis=1).astype(np.int32))
+        one = dict(common, step_w=np.array([3.7e-4], np.float32), zero_w=np.array([119], np.int32), w_group=-1)
+        rep = dict(common, step_w=np.full(N, 3.7e-4, np.float32), zero_w=np.full(N, 119, np.int32))
+        ref = orc.w8a8_output_direct(xq, wq, 0.0123, 141, rep["step_w"], rep["zero_w"], common["bias"])
+        _, got, _ = gpu_gemm(B, xq, wq, want_i32=False, deq=one)
+        assert np.array_equal(host(got), ref.astype(np.float32))
+        _, got_rep, _ = gpu_gemm(B, xq, wq, want_i32=False, deq=rep)
+        assert np.array_equal(host(got_rep), host(got))
 
 
 def test_gemm_with_activation_quantizer_in_front(B, orc):
@@ -601,8 +654,8 @@ def test_gemm_with_activation_quantizer_in_front(B, orc):
     xq, rs, csx = e(B.aweq_panel_bytes(T, K), dtype=torch.int8), e(T, dtype=torch.int32), e(K, dtype=torch.int64)
     out, csa = e(T, N, dtype=torch.int32), e(N, dtype=torch.int64)
     B.aweq_w8a8_gemm(dev(X), B.AWEQ_F16, T, K, K, dev(inv_s), dev(np.array([step], np.float32)),
-                     dev(np.array([zero], np.int32)), xq, rs, csx, dev(to_panels(wq)), N, None, None, None, None, out, None,
-                     B.AWEQ_F16, N, csa, None, None)
+                     dev(np.array([zero], np.int32)), xq, rs, csx, dev(to_panels(wq)), N, None, None, 0, None, None, out, None,
+                     B.AWEQ_F16, N, csa, qa_ws(B, T, K), None)
     assert np.array_equal(from_panels(host(xq), T, K), a["xq"]) and np.array_equal(host(rs), a["rowsum_x"])
     ref = orc.gemm_i8(a["xq"], wq)
     assert np.array_equal(host(out), ref)
@@ -752,6 +805,6 @@ def test_calibration_without_the_forward(B, orc, dtype, T, K, N, has_bias):
     np.testing.assert_allclose(lean["bias_out"], b_ref, rtol=1e-5, atol=1e-5 * np.max(np.abs(d_ref)))
     # the sums-only activation quantizer alone
     rs, cs = e(T, dtype=torch.int32), e(K, dtype=torch.int64)
-    B.aweq_quant_act(dev(X), dtc(B, X), T, K, K, dev(host(t["inv_s"])), t["act_step"], t["act_zero"], None, rs, cs)
+    B.aweq_quant_act(dev(X), dtc(B, X), T, K, K, dev(host(t["inv_s"])), t["act_step"], t["act_zero"], None, rs, cs, qa_ws(B, T, K))
     a = orc.quant_act(X, host(t["inv_s"]), lean["act_step"][0], int(lean["act_zero"][0]))
     assert np.array_equal(host(rs), a["rowsum_x"]) and np.array_equal(host(cs), a["colsum_xq"])

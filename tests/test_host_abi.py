@@ -45,14 +45,16 @@ def test_workspace_sizes(B):
     # stats partials: (min, max fp32 + sum fp64) per column per row slice; bounded and monotone in K
     a = B.aweq_workspace_size(B.OP_CALIB_STATS, 262144, 4096)
     b = B.aweq_workspace_size(B.OP_CALIB_STATS, 262144, 16384)
-    assert a % (4096 * 16) == 0 and 0 < a <= 64 << 20 and 0 < b <= 64 << 20
-    assert B.aweq_workspace_size(B.OP_CALIB_STATS, 8, 8) == 8 * 16
+    assert (a - 16) % (4096 * 16) == 0 and 0 < a <= 64 << 20 and 0 < b <= 64 << 20   # + the merge kernel's control words
+    assert B.aweq_workspace_size(B.OP_CALIB_STATS, 8, 8) == 8 * 16 + 16
     assert B.aweq_workspace_size(B.OP_CALIB_STATS, 0, 8) == 0
     assert B.aweq_workspace_size(B.OP_QUANT_WEIGHT, 4096, 4096) >= 8
     for op in (B.OP_EQUALIZE, B.OP_BIAS_CORRECT):
         assert B.aweq_workspace_size(op, 4096, 4096, 4096) == 0
-    # the fused GEMM's output statistics: a key pair and a 64-bit sum per output channel
-    assert B.aweq_workspace_size(B.OP_W8A8_GEMM, 4096, 4096, 11008) == 11008 * 16
+    # the fused GEMM's output statistics (a key pair and a 64-bit sum per output channel) or stage 4a's
+    # partial sums, whichever is larger
+    assert B.aweq_workspace_size(B.OP_W8A8_GEMM, 64, 64, 11008) == 11008 * 16
+    assert B.aweq_workspace_size(B.OP_W8A8_GEMM, 262144, 4096, 4096) == B.aweq_workspace_size(B.OP_QUANT_ACT, 262144, 4096)
 
 
 P = 0x10000  # a fake, 16-byte aligned, never dereferenced "device pointer"
@@ -103,7 +105,7 @@ def test_calib_stats_static_argument_errors(B):
 
 def test_equalize_argument_errors(B):
     ok = dict(xmin=P, xmax=P, xsum=P, count=10, wmin=P, wmax=P, K=64, enable_awe=1, s=P, inv_s=P, W=P, W_hat=P,
-              dt=B.AWEQ_F16, N=8, ldw=64, prev_scale=None, xhat_range=P, mu_xhat=P, act_step=P, act_zero=P)
+              dt=B.AWEQ_F16, N=8, ldw=64, ldwh=64, prev_scale=None, xhat_range=P, mu_xhat=P, act_step=P, act_zero=P)
     call = lambda **kw: B.aweq_equalize(**{**ok, **kw})
     assert _code(call, s=None) == "AWEQ_ERR_NULL"
     assert _code(call, xsum=None) == "AWEQ_ERR_NULL"  # mu_xhat asked without sums
@@ -113,6 +115,8 @@ def test_equalize_argument_errors(B):
     assert _code(call, count=0) == "AWEQ_ERR_SHAPE"
     assert _code(call, dt=B.AWEQ_I8) == "AWEQ_ERR_DTYPE"
     assert _code(call, W=P + 4) == "AWEQ_ERR_ALIGN"
+    assert _code(call, ldwh=32) == "AWEQ_ERR_SHAPE"      # the folded weight has a pitch of its own
+    assert _code(call, ldwh=68) == "AWEQ_ERR_ALIGN"
 
 
 def test_quant_weight_argument_errors(B):
@@ -133,9 +137,12 @@ def test_quant_weight_argument_errors(B):
 
 def test_gemm_and_quant_act_argument_errors(B):
     ok = dict(X=P, x_dt=B.AWEQ_F16, T=64, K=64, ldx=64, inv_s=P, act_step=P, act_zero=P, xq=P, rowsum_x=P,
-              colsum_xq=P, wq=P, N=32, step_w=P, zero_w=P, rowsum_w=P, bias=None, out_i32=P, out_deq=None,
-              out_dt=B.AWEQ_F16, ldo=32, colsum_acc=P)
+              colsum_xq=P, wq=P, N=32, step_w=P, zero_w=P, w_group=0, rowsum_w=P, bias=None, out_i32=P, out_deq=None,
+              out_dt=B.AWEQ_F16, ldo=32, colsum_acc=P, ws=P, ws_bytes=1 << 20)
     call = lambda **kw: B.aweq_w8a8_gemm(**{**ok, **kw})
+    assert _code(call, w_group=128) == "AWEQ_ERR_GROUP"   # the int8 path has per-channel or per-tensor weight scales
+    assert _code(call, ws=None, ws_bytes=0) == "AWEQ_ERR_WORKSPACE"   # stage 4a's column sums need it
+    assert B.aweq_workspace_size(B.OP_W8A8_GEMM, 64, 64, 32) >= B.aweq_workspace_size(B.OP_QUANT_ACT, 64, 64) > 0
     assert _code(call, wq=None) == "AWEQ_ERR_NULL"
     assert _code(call, xq=None) == "AWEQ_ERR_NULL"        # float input needs the code buffer
     assert _code(call, inv_s=None) == "AWEQ_ERR_NULL"
@@ -147,6 +154,12 @@ def test_gemm_and_quant_act_argument_errors(B):
     assert _code(call, K=65536, ldx=65536) == "AWEQ_ERR_SHAPE"
     qa = dict(X=P, dt=B.AWEQ_F16, T=8, K=64, ldx=64, inv_s=P, act_step=P, act_zero=P, xq=P, rowsum_x=None, colsum_xq=None)
     qcall = lambda **kw: B.aweq_quant_act(**{**qa, **kw})
+    assert _code(qcall, colsum_xq=P) == "AWEQ_ERR_WORKSPACE"          # column sums go through per-slice partials
+    assert _code(qcall, colsum_xq=P, ws=P, ws_bytes=8) == "AWEQ_ERR_WORKSPACE"
+    assert _code(qcall, K=1024, ldx=1024, rowsum_x=P) == "AWEQ_ERR_WORKSPACE"   # row sums over several column chunks
+    # per-slice int32 column sums plus per-chunk int32 row sums; no row-sum partials for one chunk
+    assert B.aweq_workspace_size(B.OP_QUANT_ACT, 262144, 4096) == 1024 * 4096 * 4 + 8 * 262144 * 4
+    assert B.aweq_workspace_size(B.OP_QUANT_ACT, 64, 512) == 64 // 32 * 512 * 4
     assert _code(qcall, act_step=None) == "AWEQ_ERR_NULL"
     assert _code(qcall, xq=None) == "AWEQ_ERR_NULL"           # no codes and no sums asked for: nothing to do
     assert _code(qcall, dt=B.AWEQ_I8) == "AWEQ_ERR_DTYPE"
@@ -161,6 +174,7 @@ def test_bias_correct_argument_errors(B):
     assert _code(call, colsum_acc=None) == "AWEQ_ERR_NULL"          # neither the GEMM's sums nor the codes to form them from
     assert _code(call, colsum_acc=None, codes=P, bits=4) == "AWEQ_ERR_BITS"
     assert _code(call, colsum_acc=None, codes=P, group=128) == "AWEQ_ERR_BITS"
+    assert _code(call, group=128) == "AWEQ_ERR_GROUP"
     assert _code(call, count=0) == "AWEQ_ERR_SHAPE"
     assert _code(call, mode=7) == "AWEQ_ERR_SHAPE"
     assert _code(call, mode=B.BIAS_WEIGHT_ONLY) == "AWEQ_ERR_NULL"  # needs codes
@@ -232,13 +246,14 @@ def test_wonly_gemm_argument_errors(B):
 
 def test_fold_quant_weight_argument_errors(B):
     P = 0x10000
-    ok = dict(W=P, dt=B.AWEQ_F16, N=8, K=64, ldw=64, s=P, W_hat=P, bits=8, codes=P, step=P, zero=P, rowsum_w=P, stream=0)
+    ok = dict(W=P, dt=B.AWEQ_F16, N=8, K=64, ldw=64, s=P, W_hat=P, ldwh=64, bits=8, codes=P, step=P, zero=P, rowsum_w=P, stream=0)
     call = lambda **kw: B.aweq_fold_quant_weight(**{**ok, **kw})
     assert _code(call, s=None) == "AWEQ_ERR_NULL"
     assert _code(call, bits=5) == "AWEQ_ERR_BITS"
     assert _code(call, bits=4) == "AWEQ_ERR_BITS"            # row sums are an int8 notion
     assert _code(call, K=24584, ldw=24584) == "AWEQ_ERR_SHAPE"
     assert _code(call, W=P + 8) == "AWEQ_ERR_ALIGN"
+    assert _code(call, ldwh=56) == "AWEQ_ERR_SHAPE"
 
 
 def test_fused_gemm_argument_errors(B):

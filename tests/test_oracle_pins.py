@@ -160,6 +160,33 @@ def test_scale_guards(orc):
     assert s[4] == 1.0
 
 
+def test_absmax_scale_golden_and_closed_forms(orc):
+    """The abs-max variant of the difficulty (the definition the method replaces): channel quantity
+    max |.| instead of max - min, same closed form."""
+    g = read_golden("absmax_scale.txt")
+    f = lambda k: np.array(g[k], np.float32)
+    m_x, m_w = orc.channel_absmax(f("x_min"), f("x_max")), orc.channel_absmax(f("w_min"), f("w_max"))
+    assert m_x.tolist() == g["m_x"] and m_w.tolist() == g["m_w"]
+    s, inv_s, st = orc.scales(m_x, m_w)
+    assert s.tolist() == g["s"] and st == 0
+    assert (m_x / s).tolist() == g["equalised_absmax"] and (s * m_w).tolist() == g["equalised_absmax"]
+    # brute force on data: m = max |x| over the rows of each column; a dropped abs or a min/max swap fails
+    rng = np.random.default_rng(77)
+    X = (rng.standard_normal((200, 24)) * rng.uniform(0.1, 30, 24) + rng.uniform(-5, 5, 24)).astype(np.float16)
+    sx = orc.col_stats(X)
+    m = orc.channel_absmax(sx["cmin"], sx["cmax"])
+    assert np.array_equal(m, np.abs(X.astype(np.float32)).max(axis=0))
+    # a channel that is symmetric about zero has m = r / 2, so both definitions give the same scale there
+    r_x, _, _ = orc.ranges(np.float32([-4, -2]), np.float32([4, 2]))
+    r_w, _, _ = orc.ranges(np.float32([-0.5, -1]), np.float32([0.5, 1]))
+    sr, _, _ = orc.scales(r_x, r_w)
+    sm, _, _ = orc.scales(orc.channel_absmax(np.float32([-4, -2]), np.float32([4, 2])),
+                          orc.channel_absmax(np.float32([-0.5, -1]), np.float32([0.5, 1])))
+    assert np.array_equal(sr, sm)
+    # and they differ for a shifted channel: range 2 around 10 has m = 11
+    assert orc.channel_absmax(np.float32([9]), np.float32([11]))[0] == 11.0
+
+
 def test_fold_rounds_in_two_steps(orc):
     """The folded binary16 weight is the fp32 product rounded to binary16 (Sec. 3.1, Eq. 3, with
     the model stored as FP16, Sec. 2): two roundings.  Special case that reduces to a library
@@ -242,6 +269,33 @@ def test_quantizer_golden(orc, name):
     if "stored" in g:
         packed = orc.pack_codes(u.astype(np.uint8)[None, :], 8)
         assert packed[0].tolist() == [int(v) for v in g["stored"]]
+
+
+def test_quantizer_big_quotients_golden(orc):
+    """Quotients at and beyond 2^24 and 2^30 (Eq. 1 with a Step / Z that do not come from the data):
+    the flag is raised from |round(x / Step)| >= 2^24 on, the rounded quotient saturates at +-2^30
+    before Z is added, the sum is an exact integer sum, then the clamp."""
+    g = read_golden("quantizer_bigquot.txt")
+    step, bits = np.float32(g["step"][0]), int(g["bits"][0])
+    for case in "abcd":
+        zero = int(g[case + "_zero"][0])
+        x = np.array(g[case + "_x"], np.float32)
+        u, st = orc.quant_values(x, step, zero, bits)
+        assert u.tolist() == [int(v) for v in g[case + "_codes"]], case
+        if case + "_flag" in g:
+            for xi, fl in zip(x, g[case + "_flag"]):
+                _, st1 = orc.quant_values(np.array([xi], np.float32), step, zero, bits)
+                assert bool(st1 & orc.ST_BIGQUOT) == bool(fl), (case, xi)
+    # the same through the activation quantizer (its status word and sums), binary32 input
+    X = np.array([[16777216.0, 3.0, -2.0, 0.0, 1.0, 2.0, 4.0, 5.0]], np.float32)
+    a = orc.quant_act(X, np.ones(8, np.float32), 1.0, 100 - 2 ** 24)
+    assert a["status"] & orc.ST_BIGQUOT and a["xq"][0, 0] == 100 - 128 and np.all(a["xq"][0, 1:] == -128)
+    a = orc.quant_act(X / np.float32(2), np.ones(8, np.float32), 1.0, 100 - 2 ** 24)
+    assert not a["status"] & orc.ST_BIGQUOT
+    # a Step whose quotient only just reaches 2^24 after the rounding of the division still flags:
+    # x / Step = 2^24 - 0.5 rounds (ties to even) to 2^24 in binary32
+    u, st = orc.quant_values(np.array([16777215.5 * 3.0], np.float64).astype(np.float32), np.float32(3.0), 0, 8)
+    assert st & orc.ST_BIGQUOT
 
 
 @pytest.mark.parametrize("bits", [8, 4, 3])
