@@ -559,7 +559,8 @@ def mfma_probe(torch, dev, iters=20000, reps=12):
     st = torch.cuda.current_stream().cuda_stream
     res = {}
     for mode, name, ops in ((0, "constant_bytes", 65536), (1, "random_bytes", 65536), (2, "small_signed_codes", 65536),
-                            (3, "f16_32x32x16_random_values", 32768)):
+                            (3, "f16_32x32x16_random_values", 32768), (4, "small_codes_first_operand_random_second", 65536),
+                            (5, "random_first_operand_small_codes_second", 65536)):
         for _ in range(reps):  # the clock settles over a few tens of milliseconds
             assert lib.bench_probe_mfma_clock(iters, mode, out.data_ptr(), st) == 0
         cyc, ticks = int(out[0].item()), int(out[1].item())

@@ -73,6 +73,10 @@ __global__ __launch_bounds__(256) void mfma_clock_probe(int iters, int operand_m
                     if (operand_mode == 2) {  // small signed codes, like equalised activations / weights
                         va = (unsigned)((int)(va % 9) - 4) & 0xff;
                         vb = (unsigned)((int)(vb % 33) - 16) & 0xff;
+                    } else if (operand_mode == 4) {  // first operand small codes, second operand any byte
+                        va = (unsigned)((int)(va % 9) - 4) & 0xff;
+                    } else if (operand_mode == 5) {  // the other way round
+                        vb = (unsigned)((int)(vb % 9) - 4) & 0xff;
                     }
                     ra |= va << (8 * byte);
                     rb |= vb << (8 * byte);
@@ -142,11 +146,11 @@ __global__ __launch_bounds__(256) void stream_probe(const sv4i* __restrict__ in,
 // out[3] (device, uint64): shader-clock cycles of one wavefront's loop, 100 MHz reference ticks of the
 // same interval, a checksum.  operand_mode 0: constant bytes, 1: uniformly random bytes, 2: small signed
 // codes (int8 32x32x32 MFMA, 65536 ops each); 3: the binary16 32x32x16 MFMA (32768 flop each) on
-// activation- and weight-like values.  One workgroup of four wavefronts per compute unit, iters x 16
+// activation- and weight-like values; 4 / 5: small codes in the first / second int8 operand only, any byte in the other.  One workgroup of four wavefronts per compute unit, iters x 16
 // instructions per wavefront.  Returns 0 or a negative number (bad argument / launch refused).
 extern "C" int bench_probe_mfma_clock(int iters, int operand_mode, uint64_t* out, void* stream)
 {
-    if (!out || iters <= 0 || iters > (1 << 22) || operand_mode < 0 || operand_mode > 3) return -1;
+    if (!out || iters <= 0 || iters > (1 << 22) || operand_mode < 0 || operand_mode > 5) return -1;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return -2;
