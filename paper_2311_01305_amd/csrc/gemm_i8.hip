@@ -70,6 +70,8 @@ struct GemmArgs {
     int w_per_tensor;  // step_w / zero_w hold one entry for the whole weight instead of one per output channel
     int tiles_m, tiles_n, patch_m, patch_n, patches_n, n_patches;
     int n_ids;  // workgroup ids that may name a tile (whole rounds of patches over the XCDs)
+    // tiled kernel: the tile columns that do not fill a whole patch column form patches of their own shape
+    int main_pn, n_main, tail_cols, tail_pm, per_patch, n_patches_fast;
     // fused epilogues on the de-quantised binary16 output y (the next layer's calibration input)
     int act;                    // 0: none, 1: ReLU before y is rounded
     uint32_t* ykeys;            // [2 N] order-preserving keys of the column minimum / maximum of y
@@ -319,17 +321,26 @@ __device__ __forceinline__ void wait_vm()
 
 // workgroup id -> output tile (false: the id names no tile).  Ids go round-robin over the XCDs,
 // so id % 8 names the XCD; each XCD walks its own sequence of patch_m x patch_n patches.
-__device__ __forceinline__ bool tile_of(const GemmArgs& g, int vb, int& tile_m, int& tile_n)
+// The last tile columns, when they do not fill a patch column, are walked as patches of their own
+// shape (tail_pm x tail_cols, as many tiles as fit 32): a ragged patch would leave part of the XCD's
+// workgroups without a tile, they would run ahead to their next id and the XCD's workgroups would
+// stop walking K together, which is what lets them share operand panels in the L2.
+__host__ __device__ __forceinline__ bool tile_of(const GemmArgs& g, int vb, int& tile_m, int& tile_n)
 {
     const int xcd = vb % kXcds, seq = vb / kXcds;
-    const int per_patch = g.patch_m * g.patch_n;
-    const int patch = (seq / per_patch) * kXcds + xcd;
-    if (patch >= g.n_patches) return false;
-    const int within = seq % per_patch;
-    const int pm = patch / g.patches_n, pn = patch % g.patches_n;
-    tile_m = pm * g.patch_m + within % g.patch_m;
-    tile_n = pn * g.patch_n + within / g.patch_m;
-    return tile_m < g.tiles_m && tile_n < g.tiles_n;
+    const int patch = (seq / g.per_patch) * kXcds + xcd;
+    if (patch >= g.n_patches_fast) return false;
+    const int within = seq % g.per_patch;
+    if (patch < g.n_main) {
+        const int pm = patch / g.main_pn, pn = patch % g.main_pn;
+        tile_m = pm * g.patch_m + within % g.patch_m;
+        tile_n = pn * g.patch_n + within / g.patch_m;
+        return tile_m < g.tiles_m && tile_n < g.tiles_n;
+    }
+    if (within >= g.tail_pm * g.tail_cols) return false;
+    tile_m = (patch - g.n_main) * g.tail_pm + within % g.tail_pm;
+    tile_n = g.main_pn * g.patch_n + within / g.tail_pm;
+    return tile_m < g.tiles_m;
 }
 
 // DEQ: 0 none, 1 fp32, 2 fp16.  Persistent: the grid is one workgroup per compute unit
@@ -824,9 +835,17 @@ static int plan_gemm(GemmArgs& g, int64_t T, int64_t N, int64_t K, int64_t& bloc
     const int64_t patches_m = cdiv(tiles_m, g.patch_m);
     g.n_patches = (int)(patches_m * g.patches_n);
     const int64_t rounds = cdiv(g.n_patches, kXcds);
-    blocks = rounds * kXcds * g.patch_m * g.patch_n;
+    blocks = rounds * kXcds * g.patch_m * g.patch_n;   // grid of the generic kernel
     if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
-    g.n_ids = (int)blocks;
+    // the tiled kernel's walk: whole patch columns first, then the remaining tile columns as patches of their own
+    g.per_patch = g.patch_m * g.patch_n;
+    g.tail_cols = (int)(tiles_n % g.patch_n);
+    g.main_pn = (int)(tiles_n / g.patch_n);
+    g.tail_pm = g.tail_cols ? g.per_patch / g.tail_cols : 0;
+    if (g.tail_cols && g.tail_pm > tiles_m) g.tail_pm = (int)tiles_m;
+    g.n_main = (int)(patches_m * g.main_pn);
+    g.n_patches_fast = g.n_main + (g.tail_cols ? (int)cdiv(tiles_m, g.tail_pm) : 0);
+    g.n_ids = (int)(cdiv(g.n_patches_fast, kXcds) * kXcds * g.per_patch);   // <= blocks
     return AWEQ_OK;
 }
 
@@ -858,8 +877,9 @@ static int raise_lds_limit(const void* fn, int dev, int bytes)
     return AWEQ_OK;
 }
 
-static int launch_fast(const void* fn, GemmArgs& g, int64_t blocks, hipStream_t st)
+static int launch_fast(const void* fn, GemmArgs& g, hipStream_t st)
 {
+    const int64_t blocks = g.n_ids;
     int dev = 0, cus = 0;
     if (device_cus(dev, cus) != AWEQ_OK || raise_lds_limit(fn, dev, fast::kLds) != AWEQ_OK) return AWEQ_ERR_LAUNCH;
     void* args[] = {&g};
@@ -981,7 +1001,7 @@ extern "C" int aweq_w8a8_gemm(const void* X, aweq_dtype x_dt, int64_t T, int64_t
         AWEQ_PICK(true, 1, true) AWEQ_PICK(true, 1, false) AWEQ_PICK(false, 1, true) AWEQ_PICK(false, 1, false)
         AWEQ_PICK(true, 2, true) AWEQ_PICK(true, 2, false) AWEQ_PICK(false, 2, true) AWEQ_PICK(false, 2, false)
 #undef AWEQ_PICK
-        return launch_fast(fn, g, blocks, st);
+        return launch_fast(fn, g, st);
     }
     const size_t lds_bytes = 2 * 2 * kTileBytes;  // 64 KiB
     int dev = 0, cus = 0;
@@ -1046,7 +1066,7 @@ extern "C" int aweq_w8a8_gemm_fused(const int8_t* xq, int64_t T, int64_t K, cons
 #define AWEQ_PICK(E, S) if (epi == E && store == S) fn = reinterpret_cast<const void*>(fast::gemm_i8_fast<false, 2, true, E, S>);
     AWEQ_PICK(1, true) AWEQ_PICK(1, false) AWEQ_PICK(2, true) AWEQ_PICK(2, false) AWEQ_PICK(3, true) AWEQ_PICK(3, false)
 #undef AWEQ_PICK
-    const int rc = launch_fast(fn, g, blocks, st);
+    const int rc = launch_fast(fn, g, st);
     if (rc != AWEQ_OK) return rc;
     if (want_stats)
         fused_stats_finish<<<(unsigned)cdiv(N, 256), 256, 0, st>>>(g.ykeys, g.yfix, N, T, ycmin, ycmax, ycsum, ycount, accumulate, status);

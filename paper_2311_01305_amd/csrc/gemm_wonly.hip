@@ -50,7 +50,9 @@ struct Args {
     void* out;
     int64_t ldo;
     int64_t T, N, K;
-    int tiles_m, tiles_n, patch_m, patch_n, patches_n, n_patches;
+    int tiles_m, tiles_n, patch_m, patch_n, n_patches;
+    // the tile columns that do not fill a whole patch column form patches of their own shape
+    int main_pn, n_main, tail_cols, tail_pm, per_patch;
 };
 
 // chunk swizzle for 128-byte tile rows: rows sharing LDS banks get distinct chunk positions
@@ -162,13 +164,21 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(Args g)
     const int wm = wave >> 2, wn = wave & 3;
     const int b = blockIdx.x;
     const int xcd = b % kXcds, seq = b / kXcds;
-    const int per_patch = g.patch_m * g.patch_n;
-    const int patch = (seq / per_patch) * kXcds + xcd;
+    const int patch = (seq / g.per_patch) * kXcds + xcd;
     if (patch >= g.n_patches) return;
-    const int within = seq % per_patch;
-    const int pm = patch / g.patches_n, pn = patch % g.patches_n;
-    const int tile_m = pm * g.patch_m + within % g.patch_m;
-    const int tile_n = pn * g.patch_n + within / g.patch_m;
+    const int within = seq % g.per_patch;
+    int tile_m, tile_n;
+    if (patch < g.n_main) {
+        const int pm = patch / g.main_pn, pn = patch % g.main_pn;
+        tile_m = pm * g.patch_m + within % g.patch_m;
+        tile_n = pn * g.patch_n + within / g.patch_m;
+    } else {
+        // the last, incomplete patch column: patches of tail_pm x tail_cols tiles, so that an XCD's 32
+        // workgroups still start together and walk K together (a ragged patch would leave some without work)
+        if (within >= g.tail_pm * g.tail_cols) return;
+        tile_m = (patch - g.n_main) * g.tail_pm + within % g.tail_pm;
+        tile_n = g.main_pn * g.patch_n + within / g.tail_pm;
+    }
     if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
 
@@ -410,11 +420,16 @@ extern "C" int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t 
     g.patch_n = (int)(tiles_n < want_n ? tiles_n : want_n);
     g.patch_m = 32 / g.patch_n;
     if (g.patch_m > tiles_m) g.patch_m = (int)tiles_m;
-    g.patches_n = (int)cdiv(tiles_n, g.patch_n);
     const int64_t patches_m = cdiv(tiles_m, g.patch_m);
-    g.n_patches = (int)(patches_m * g.patches_n);
+    g.per_patch = g.patch_m * g.patch_n;
+    g.tail_cols = (int)(tiles_n % g.patch_n);
+    g.main_pn = (int)(tiles_n / g.patch_n);
+    g.tail_pm = g.tail_cols ? g.per_patch / g.tail_cols : 0;
+    if (g.tail_cols && g.tail_pm > tiles_m) g.tail_pm = (int)tiles_m;
+    g.n_main = (int)(patches_m * g.main_pn);
+    g.n_patches = g.n_main + (g.tail_cols ? (int)cdiv(tiles_m, g.tail_pm) : 0);
     const int64_t rounds = cdiv(g.n_patches, wonly::kXcds);
-    const int64_t blocks = rounds * wonly::kXcds * g.patch_m * g.patch_n;
+    const int64_t blocks = rounds * wonly::kXcds * g.per_patch;
     if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
 
     const void* fn = out_dt == AWEQ_F16 ? reinterpret_cast<const void*>(wonly::gemm_f16_kernel<true>)
