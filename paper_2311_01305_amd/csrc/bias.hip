@@ -34,9 +34,12 @@ __device__ __forceinline__ void load_w8(const void* row, int64_t u, float x[8])
 // colsum_acc[n] = sum_t acc[t,n] comes from the GEMM, or - by the same linearity, as exact integers -
 // from the weight codes: sum_t sum_k xq[t,k] wq[n,k] = sum_k wq[n,k] colsum_xq[k] (wq given, colsum_acc NULL),
 // so that calibration does not have to run the forward.
+// A block takes kBiasRows output channels at once: mu_xhat and colsum_xq (and their sum over k, which every
+// channel needs) are read once per block instead of once per channel.
+constexpr int kBiasRows = 8;
 template <bool F16>
 __global__ __launch_bounds__(kBiasBlock) void bias_w8a8_kernel(
-    const void* __restrict__ W_hat, int64_t K, int64_t ldw, const float* __restrict__ mu_xhat, uint64_t count,
+    const void* __restrict__ W_hat, int64_t N, int64_t K, int64_t ldw, const float* __restrict__ mu_xhat, uint64_t count,
     const long long* __restrict__ colsum_acc, const long long* __restrict__ colsum_xq,
     const int32_t* __restrict__ rowsum_w, const float* __restrict__ act_step, const int32_t* __restrict__ act_zero,
     const float* __restrict__ step_w, const int32_t* __restrict__ zero_w, const float* __restrict__ bias_in,
@@ -45,47 +48,61 @@ __global__ __launch_bounds__(kBiasBlock) void bias_w8a8_kernel(
 {
     __shared__ double slot_d[kBiasBlock / kWave];
     __shared__ long long slot_l[kBiasBlock / kWave];
-    const int64_t n = blockIdx.x;
-    const int64_t N = gridDim.x;
-    const char* row = reinterpret_cast<const char*>(W_hat) + (size_t)n * ldw * (F16 ? 2 : 4);
-    double acc = 0.0;
-    long long tot = 0, ca = 0;
+    const int64_t n0 = (int64_t)blockIdx.x * kBiasRows;
+    const int rows = (int)min((int64_t)kBiasRows, N - n0);
+    double acc[kBiasRows];
+    long long ca[kBiasRows];
+#pragma unroll
+    for (int r = 0; r < kBiasRows; ++r) { acc[r] = 0.0; ca[r] = 0; }
+    long long tot = 0;
     for (int64_t u = threadIdx.x; u < K / 8; u += kBiasBlock) {
-        float w[8];
-        load_w8<F16>(row, u, w);
         const Float4 m0 = *reinterpret_cast<const Float4*>(mu_xhat + u * 8);
         const Float4 m1 = *reinterpret_cast<const Float4*>(mu_xhat + u * 8 + 4);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            acc += (double)w[i] * (double)m0.f[i];
-            acc += (double)w[4 + i] * (double)m1.f[i];
-        }
         long long cx[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) { cx[i] = colsum_xq[u * 8 + i]; tot += cx[i]; }
-        if (wq) {
-            // unit u of row n in the K-panel layout: panel u / 8, bytes 8 (u % 8) ..
-            const uint2 v = *reinterpret_cast<const uint2*>(wq + ((u >> 3) * N + n) * kPanel + (u & 7) * 8);
+#pragma unroll
+        for (int r = 0; r < kBiasRows; ++r) {
+            if (r >= rows) break;
+            const char* row = reinterpret_cast<const char*>(W_hat) + (size_t)(n0 + r) * ldw * (F16 ? 2 : 4);
+            float w[8];
+            load_w8<F16>(row, u, w);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                ca += (long long)(int8_t)((v.x >> (8 * i)) & 0xff) * cx[i];
-                ca += (long long)(int8_t)((v.y >> (8 * i)) & 0xff) * cx[4 + i];
+                acc[r] += (double)w[i] * (double)m0.f[i];
+                acc[r] += (double)w[4 + i] * (double)m1.f[i];
+            }
+            if (wq) {
+                // unit u of row n in the K-panel layout: panel u / 8, bytes 8 (u % 8) ..
+                const uint2 v = *reinterpret_cast<const uint2*>(wq + ((u >> 3) * N + n0 + r) * kPanel + (u & 7) * 8);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    ca[r] += (long long)(int8_t)((v.x >> (8 * i)) & 0xff) * cx[i];
+                    ca[r] += (long long)(int8_t)((v.y >> (8 * i)) & 0xff) * cx[4 + i];
+                }
             }
         }
     }
-    acc = block_allreduce<kBiasBlock / kWave>(acc, OpAdd(), slot_d);
     tot = block_allreduce<kBiasBlock / kWave>(tot, OpAdd(), slot_l);
-    if (wq) ca = block_allreduce<kBiasBlock / kWave>(ca, OpAdd(), slot_l);
-    if (threadIdx.x == 0) {
-        const long long T = (long long)count;
-        const long long zx = (long long)*act_zero - 128;
-        const int64_t pi = w_per_tensor ? 0 : n;   // one (Step, Z) for the tensor, or one per output channel
-        const long long zw = (long long)zero_w[pi] - 128;
-        const long long a = (wq ? ca : colsum_acc[n]) - T * zx * (long long)rowsum_w[n] - zw * tot + T * K * zx * zw;
-        const double yq = (double)*act_step * (double)step_w[pi] * (double)a / (double)T;
-        const double d = acc - yq;
-        delta[n] = (float)d;
-        bias_out[n] = (float)((bias_in ? (double)bias_in[n] : 0.0) + (enable_bc ? d : 0.0));
+    const long long T = (long long)count;
+    const long long zx = (long long)*act_zero - 128;
+    const double sx = (double)*act_step;
+#pragma unroll
+    for (int r = 0; r < kBiasRows; ++r) {
+        if (r >= rows) break;    // (block-uniform)
+        const double a_r = block_allreduce<kBiasBlock / kWave>(acc[r], OpAdd(), slot_d);
+        long long c_r = 0;
+        if (wq) c_r = block_allreduce<kBiasBlock / kWave>(ca[r], OpAdd(), slot_l);
+        if (threadIdx.x == 0) {
+            const int64_t n = n0 + r;
+            const int64_t pi = w_per_tensor ? 0 : n;   // one (Step, Z) for the tensor, or one per output channel
+            const long long zw = (long long)zero_w[pi] - 128;
+            const long long a = (wq ? c_r : colsum_acc[n]) - T * zx * (long long)rowsum_w[n] - zw * tot + T * K * zx * zw;
+            const double yq = sx * (double)step_w[pi] * (double)a / (double)T;
+            const double d = a_r - yq;
+            delta[n] = (float)d;
+            bias_out[n] = (float)((bias_in ? (double)bias_in[n] : 0.0) + (enable_bc ? d : 0.0));
+        }
     }
 }
 
@@ -181,10 +198,10 @@ extern "C" int aweq_bias_correct(int mode, const void* W_hat, aweq_dtype dt, int
         const long long* ca = reinterpret_cast<const long long*>(colsum_acc);
         const long long* cx = reinterpret_cast<const long long*>(colsum_xq);
         if (f16)
-            bias_w8a8_kernel<true><<<(unsigned)N, kBiasBlock, 0, st>>>(W_hat, K, ldw, mu_xhat, count, ca, cx, rowsum_w, act_step,
+            bias_w8a8_kernel<true><<<(unsigned)cdiv(N, kBiasRows), kBiasBlock, 0, st>>>(W_hat, N, K, ldw, mu_xhat, count, ca, cx, rowsum_w, act_step,
                                                                      act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc, wq, pt);
         else
-            bias_w8a8_kernel<false><<<(unsigned)N, kBiasBlock, 0, st>>>(W_hat, K, ldw, mu_xhat, count, ca, cx, rowsum_w, act_step,
+            bias_w8a8_kernel<false><<<(unsigned)cdiv(N, kBiasRows), kBiasBlock, 0, st>>>(W_hat, N, K, ldw, mu_xhat, count, ca, cx, rowsum_w, act_step,
                                                                       act_zero, step_w, zero_w, bias_in, delta, bias_out, enable_bc, wq, pt);
     } else if (mode == AWEQ_BIAS_WEIGHT_ONLY) {
         if (!codes) return AWEQ_ERR_NULL;

@@ -3,6 +3,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+#include <set>
+#include <utility>
+
 #include "aweq.h"
 
 namespace aweq {
@@ -15,6 +20,35 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? AWEQ_OK : AWEQ_ERR_LAUNCH; }
 inline size_t dtype_size(aweq_dtype dt) { return dt == AWEQ_F32 ? 4 : (dt == AWEQ_F16 ? 2 : 1); }
+
+constexpr int kXcdCount = 8;   // workgroup ids are dealt round-robin to the XCDs: id % 8 names the XCD
+
+// ---------------------------------------------------------------- launch helpers (host)
+// compute units of the current device, asked once per device
+inline int device_cus(int& dev, int& cus)
+{
+    constexpr int kMaxDev = 64;
+    static std::atomic<int> cached[kMaxDev];
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return AWEQ_ERR_LAUNCH;
+    cus = cached[dev].load(std::memory_order_relaxed);
+    if (cus == 0) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return AWEQ_ERR_LAUNCH;
+        cached[dev].store(cus, std::memory_order_relaxed);
+    }
+    return AWEQ_OK;
+}
+
+// the dynamic LDS limit of a kernel is raised once per (kernel, device), not per launch
+inline int raise_lds_limit(const void* fn, int dev, int bytes)
+{
+    static std::mutex mu;
+    static std::set<std::pair<const void*, int>> done;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({fn, dev})) return AWEQ_OK;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return AWEQ_ERR_LAUNCH;
+    done.insert({fn, dev});
+    return AWEQ_OK;
+}
 
 // K-panel layout of an int8 matrix [rows x K] (the GEMM operands): panel p holds bytes
 // 64 p .. 64 p + 63 of every row, rows back to back; columns past K in the last panel are 0.

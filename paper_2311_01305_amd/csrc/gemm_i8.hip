@@ -25,11 +25,7 @@
 // Workgroups are numbered so that the ones resident on one XCD (which share an L2) form a
 // compact patch of the output.
 #include "common.hpp"
-#include <atomic>
-#include <mutex>
-#include <set>
 #include <type_traits>
-#include <utility>
 
 namespace aweq {
 
@@ -851,32 +847,6 @@ static int plan_gemm(GemmArgs& g, int64_t T, int64_t N, int64_t K, int64_t& bloc
 
 // persistent launch of a fast-kernel instantiation: one workgroup per compute unit (a multiple of
 // 8, so that id % 8 stays the XCD)
-// compute units of the current device, asked once per device
-static int device_cus(int& dev, int& cus)
-{
-    constexpr int kMaxDev = 64;
-    static std::atomic<int> cached[kMaxDev];
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return AWEQ_ERR_LAUNCH;
-    cus = cached[dev].load(std::memory_order_relaxed);
-    if (cus == 0) {
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return AWEQ_ERR_LAUNCH;
-        cached[dev].store(cus, std::memory_order_relaxed);
-    }
-    return AWEQ_OK;
-}
-
-// the dynamic LDS limit of a kernel is raised once per (kernel, device), not per launch
-static int raise_lds_limit(const void* fn, int dev, int bytes)
-{
-    static std::mutex mu;
-    static std::set<std::pair<const void*, int>> done;
-    std::lock_guard<std::mutex> lock(mu);
-    if (done.count({fn, dev})) return AWEQ_OK;
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return AWEQ_ERR_LAUNCH;
-    done.insert({fn, dev});
-    return AWEQ_OK;
-}
-
 static int launch_fast(const void* fn, GemmArgs& g, hipStream_t st)
 {
     const int64_t blocks = g.n_ids;

@@ -53,6 +53,7 @@ struct Args {
     int tiles_m, tiles_n, patch_m, patch_n, n_patches;
     // the tile columns that do not fill a whole patch column form patches of their own shape
     int main_pn, n_main, tail_cols, tail_pm, per_patch;
+    int n_ids;  // workgroup ids that may name a tile (whole rounds of patches over the XCDs)
 };
 
 // chunk swizzle for 128-byte tile rows: rows sharing LDS banks get distinct chunk positions
@@ -156,57 +157,47 @@ __device__ __forceinline__ void wait_vm()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// workgroup id -> output tile (false: the id names no tile).  Ids go round-robin over the XCDs, so
+// id % 8 names the XCD; each XCD walks its own sequence of patches of 32 tiles.  The tile columns that
+// do not fill a whole patch column form patches of their own shape (tail_pm x tail_cols), so that an
+// XCD's 32 workgroups always start a patch together and walk K together (a ragged patch would leave
+// some of them without a tile).
+__device__ __forceinline__ bool tile_of(const Args& g, int vb, int& tile_m, int& tile_n)
+{
+    const int xcd = vb % kXcds, seq = vb / kXcds;
+    const int patch = (seq / g.per_patch) * kXcds + xcd;
+    if (patch >= g.n_patches) return false;
+    const int within = seq % g.per_patch;
+    if (patch < g.n_main) {
+        const int pm = patch / g.main_pn, pn = patch % g.main_pn;
+        tile_m = pm * g.patch_m + within % g.patch_m;
+        tile_n = pn * g.patch_n + within / g.patch_m;
+        return tile_m < g.tiles_m && tile_n < g.tiles_n;
+    }
+    if (within >= g.tail_pm * g.tail_cols) return false;
+    tile_m = (patch - g.n_main) * g.tail_pm + within % g.tail_pm;
+    tile_n = g.main_pn * g.patch_n + within / g.tail_pm;
+    return tile_m < g.tiles_m;
+}
+
+// Persistent: the grid is one workgroup per compute unit (a multiple of 8), workgroup b takes the ids
+// b, b + grid, b + 2 grid, ...; the first stages of its next tile are requested before the epilogue of
+// the current one starts, so the loads fly while the results are stored.
 template <bool OUT_F16>
 __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(Args g)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
-    const int b = blockIdx.x;
-    const int xcd = b % kXcds, seq = b / kXcds;
-    const int patch = (seq / g.per_patch) * kXcds + xcd;
-    if (patch >= g.n_patches) return;
-    const int within = seq % g.per_patch;
-    int tile_m, tile_n;
-    if (patch < g.n_main) {
-        const int pm = patch / g.main_pn, pn = patch % g.main_pn;
-        tile_m = pm * g.patch_m + within % g.patch_m;
-        tile_n = pn * g.patch_n + within / g.patch_m;
-    } else {
-        // the last, incomplete patch column: patches of tail_pm x tail_cols tiles, so that an XCD's 32
-        // workgroups still start together and walk K together (a ragged patch would leave some without work)
-        if (within >= g.tail_pm * g.tail_cols) return;
-        tile_m = (patch - g.n_main) * g.tail_pm + within % g.tail_pm;
-        tile_n = g.main_pn * g.patch_n + within / g.tail_pm;
-    }
-    if (tile_m >= g.tiles_m || tile_n >= g.tiles_n) return;
-    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const int stride = gridDim.x;
 
-    // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 8 rows x 128 B per
-    // instruction; lane i sits at row i / 8, chunk slot i % 8 and fetches chunk slot ^ g8(row)
-    const char* baseA = reinterpret_cast<const char*>(g.X + m0 * g.ldx);
-    const char* baseB = reinterpret_cast<const char*>(g.W + n0 * g.K);
-    uint32_t oa[4], ob[4];  // byte offsets from the tile's first row: < 256 * 2 ldx
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int row = wave * 32 + q * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ g8(row);
-        // rows past the edge re-read the last valid row; their results are never stored
-        const int64_t ra = min(m0 + row, g.T - 1) - m0, rb = min(n0 + row, g.N - 1) - n0;
-        oa[q] = (uint32_t)(ra * g.ldx * 2 + chunk * 16);
-        ob[q] = (uint32_t)(rb * g.K * 2 + chunk * 16);
-    }
+    int vb = blockIdx.x, tile_m = 0, tile_n = 0;
+    while (vb < g.n_ids && !tile_of(g, vb, tile_m, tile_n)) vb += stride;
+    if (vb >= g.n_ids) return;
+
     const int ns = (int)(g.K / BKH);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
     const uint32_t wave_off = __builtin_amdgcn_readfirstlane(wave) * 4096;
-
-    v16f acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     // fragment of K-step qq (16 values = 32 bytes per row): lane reads row lane % 32 of a 32-row
     // sub-tile, chunk 2 qq + lane / 32
@@ -218,156 +209,216 @@ __global__ __launch_bounds__(kThreads) void gemm_f16_kernel(Args g)
         offA[qq] = (wm * 128 + fr_row) * kRow + ((qq * 2 + fr_half) ^ fsw) * 16;
         offB[qq] = kLdsB + (wn * 64 + fr_row) * kRow + ((qq * 2 + fr_half) ^ fsw) * 16;
     }
-    v4i a0[4], b0[2], a1[4], b1[2];
+
+    // global -> LDS: wave w brings tile rows 32 w .. 32 w + 31 of both operands, 8 rows x 128 B per
+    // instruction; lane i sits at row i / 8, chunk slot i % 8 and fetches chunk slot ^ g8(row)
+    const char* baseA;   // the tile's first rows (wave-uniform: scalar registers)
+    const char* baseB;
+    uint32_t oa[4], ob[4];  // byte offsets from the tile's first row: < 256 * 2 ldx
+    int64_t m0, n0;
 
 #define RDA(dst, qq, i) dst[i] = *reinterpret_cast<const v4i*>(sa + offA[qq] + (i) * 32 * kRow)
 #define RDB(dst, qq, j) dst[j] = *reinterpret_cast<const v4i*>(sb + offB[qq] + (j) * 32 * kRow)
 #define DMA_A(q, s_) dma16(baseA + (int64_t)(s_) * kRow, oa[q], lds0 + ((s_) % kSlotsA) * kTile + wave_off + (q) * 1024)
 #define DMA_B(q, s_) dma16(baseB + (int64_t)(s_) * kRow, ob[q], lds0 + kLdsB + ((s_) & 1) * kTile + wave_off + (q) * 1024)
 
-    // prologue: stage 0 of both operands, stage 1 of the activations
+    // addresses of tile (tm, tn); stage 0 of both operands and stage 1 of the activations on their way
+    // (activation slots 0 and 1, weight slot 0)
+    auto start_tile = [&](int tm, int tn) {
+        m0 = (int64_t)__builtin_amdgcn_readfirstlane(tm) * BM;
+        n0 = (int64_t)__builtin_amdgcn_readfirstlane(tn) * BN;
+        baseA = reinterpret_cast<const char*>(g.X + m0 * g.ldx);
+        baseB = reinterpret_cast<const char*>(g.W + n0 * g.K);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) DMA_A(q, 0);
+        for (int q = 0; q < 4; ++q) {
+            const int row = wave * 32 + q * 8 + (lane >> 3);
+            const int chunk = (lane & 7) ^ g8(row);
+            // rows past the edge re-read the last valid row; their results are never stored
+            const int64_t ra = min(m0 + row, g.T - 1) - m0, rb = min(n0 + row, g.N - 1) - n0;
+            oa[q] = (uint32_t)(ra * g.ldx * 2 + chunk * 16);
+            ob[q] = (uint32_t)(rb * g.K * 2 + chunk * 16);
+        }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) DMA_B(q, 0);
-    if (ns > 1) {
+        for (int q = 0; q < 4; ++q) DMA_A(q, 0);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) DMA_A(q, 1);
-        wait_vm<4>();
-    } else {
-        wait_vm<0>();
-    }
-    __builtin_amdgcn_s_barrier();
-    {
-        const char* sa = lds;
-        const char* sb = lds;
+        for (int q = 0; q < 4; ++q) DMA_B(q, 0);
+        if (ns > 1) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) RDA(a0, 0, i);
-        RDB(b0, 0, 0); RDB(b0, 0, 1);
-    }
-
-    // one stage (64 values of K) = four K-steps of 8 MFMAs per wave.  F0 / F1 are the two fragment
-    // register sets; each K-step multiplies one and fetches the other.  NEXT: there is a stage
-    // s + 1 (its weights are requested here); NEXT2: there is a stage s + 2 (its activations are).
-    auto stage = [&](int s, auto next_c, auto next2_c) {
-        constexpr bool NEXT = decltype(next_c)::value;
-        constexpr bool NEXT2 = decltype(next2_c)::value;
-        const char* sa = lds + (s % kSlotsA) * kTile;
-        const char* sb = lds + (s & 1) * kTile;
-        // K-step 0: multiply F0, fetch F1.  The slots of stage s - 1 are free (every wave passed that
-        // stage's barrier): the weights of stage s + 1 and the activations of stage s + 2 go there
-        SB();
-        RDA(a1, 1, 0); RDB(b1, 1, 0); RDB(b1, 1, 1); MF(a0, b0, 0, 0);
-        SB();
-        if constexpr (NEXT) DMA_B(0, s + 1);
-        RDA(a1, 1, 1); RDA(a1, 1, 2); MF(a0, b0, 0, 1);
-        SB();
-        if constexpr (NEXT) DMA_B(1, s + 1);
-        RDA(a1, 1, 3); MF(a0, b0, 1, 0);
-        SB();
-        if constexpr (NEXT) DMA_B(2, s + 1);
-        MF(a0, b0, 1, 1);
-        SB();
-        if constexpr (NEXT) DMA_B(3, s + 1);
-        MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
-        SB();
-        // K-step 1: multiply F1, fetch F0
-        RDA(a0, 2, 0); RDB(b0, 2, 0); RDB(b0, 2, 1); MF(a1, b1, 0, 0);
-        SB();
-        if constexpr (NEXT2) DMA_A(0, s + 2);
-        RDA(a0, 2, 1); RDA(a0, 2, 2); MF(a1, b1, 0, 1);
-        SB();
-        if constexpr (NEXT2) DMA_A(1, s + 2);
-        RDA(a0, 2, 3); MF(a1, b1, 1, 0);
-        SB();
-        if constexpr (NEXT2) DMA_A(2, s + 2);
-        MF(a1, b1, 1, 1);
-        SB();
-        if constexpr (NEXT2) DMA_A(3, s + 2);
-        MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
-        SB();
-        // K-step 2: multiply F0, fetch F1
-        RDA(a1, 3, 0); RDB(b1, 3, 0); RDB(b1, 3, 1); MF(a0, b0, 0, 0);
-        SB();
-        RDA(a1, 3, 1); RDA(a1, 3, 2); MF(a0, b0, 0, 1);
-        SB();
-        RDA(a1, 3, 3); MF(a0, b0, 1, 0);
-        SB();
-        MF(a0, b0, 1, 1); MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
-        SB();
-        if constexpr (NEXT) {
-            // stage s + 1 has landed for this wave (only the 4 newest loads, the activations of stage
-            // s + 2, may still be out), its reads of stage s are done; after the barrier that holds
-            // for every wave
-            if constexpr (NEXT2) wait_vm<4>(); else wait_vm<0>();
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            SB();
-            sa = lds + ((s + 1) % kSlotsA) * kTile;
-            sb = lds + ((s + 1) & 1) * kTile;
-            // K-step 3: multiply F1, fetch F0 = K-step 0 of the next stage
-            RDA(a0, 0, 0); RDB(b0, 0, 0); RDB(b0, 0, 1); MF(a1, b1, 0, 0);
-            SB();
-            RDA(a0, 0, 1); RDA(a0, 0, 2); MF(a1, b1, 0, 1);
-            SB();
-            RDA(a0, 0, 3); MF(a1, b1, 1, 0);
-            SB();
-            MF(a1, b1, 1, 1); MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
-            SB();
-        } else {
-            MF(a1, b1, 0, 0); MF(a1, b1, 0, 1); MF(a1, b1, 1, 0); MF(a1, b1, 1, 1);
-            MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+            for (int q = 0; q < 4; ++q) DMA_A(q, 1);
         }
     };
-    int s = 0;
-    for (; s + 2 < ns; ++s) stage(s, std::true_type{}, std::true_type{});
-    if (s + 1 < ns) { stage(s, std::true_type{}, std::false_type{}); ++s; }
-    stage(s, std::false_type{}, std::false_type{});
+
+    start_tile(tile_m, tile_n);
+    if (ns > 1) wait_vm<4>(); else wait_vm<0>();
+
+    // Vector memory operations of a wave complete in the order issued.  A tile that lies inside the
+    // output issues 32 stores per wave after requesting the next tile's first stages, so "at most
+    // 32 + 4 operations pending" means stage 0 has landed while the stores (and the 4 loads of the
+    // activations' stage 1) may still be on their way.
+    constexpr int kStores = 32;
+
+    for (;;) {
+        const int64_t cm0 = m0, cn0 = n0;   // the tile being multiplied
+        v16f acc[4][2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        v4i a0[4], b0[2], a1[4], b1[2];
+
+        __builtin_amdgcn_s_barrier();   // stage 0 has landed for every wave
+        {
+            const char* sa = lds;
+            const char* sb = lds;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) RDA(a0, 0, i);
+            RDB(b0, 0, 0); RDB(b0, 0, 1);
+        }
+
+        // one stage (64 values of K) = four K-steps of 8 MFMAs per wave.  F0 / F1 are the two fragment
+        // register sets; each K-step multiplies one and fetches the other.  NEXT: there is a stage
+        // s + 1 (its weights are requested here); NEXT2: there is a stage s + 2 (its activations are).
+        auto stage = [&](int s, auto next_c, auto next2_c) {
+            constexpr bool NEXT = decltype(next_c)::value;
+            constexpr bool NEXT2 = decltype(next2_c)::value;
+            const char* sa = lds + (s % kSlotsA) * kTile;
+            const char* sb = lds + (s & 1) * kTile;
+            // K-step 0: multiply F0, fetch F1.  The slots of stage s - 1 are free (every wave passed that
+            // stage's barrier): the weights of stage s + 1 and the activations of stage s + 2 go there
+            SB();
+            RDA(a1, 1, 0); RDB(b1, 1, 0); RDB(b1, 1, 1); MF(a0, b0, 0, 0);
+            SB();
+            if constexpr (NEXT) DMA_B(0, s + 1);
+            RDA(a1, 1, 1); RDA(a1, 1, 2); MF(a0, b0, 0, 1);
+            SB();
+            if constexpr (NEXT) DMA_B(1, s + 1);
+            RDA(a1, 1, 3); MF(a0, b0, 1, 0);
+            SB();
+            if constexpr (NEXT) DMA_B(2, s + 1);
+            MF(a0, b0, 1, 1);
+            SB();
+            if constexpr (NEXT) DMA_B(3, s + 1);
+            MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
+            SB();
+            // K-step 1: multiply F1, fetch F0
+            RDA(a0, 2, 0); RDB(b0, 2, 0); RDB(b0, 2, 1); MF(a1, b1, 0, 0);
+            SB();
+            if constexpr (NEXT2) DMA_A(0, s + 2);
+            RDA(a0, 2, 1); RDA(a0, 2, 2); MF(a1, b1, 0, 1);
+            SB();
+            if constexpr (NEXT2) DMA_A(1, s + 2);
+            RDA(a0, 2, 3); MF(a1, b1, 1, 0);
+            SB();
+            if constexpr (NEXT2) DMA_A(2, s + 2);
+            MF(a1, b1, 1, 1);
+            SB();
+            if constexpr (NEXT2) DMA_A(3, s + 2);
+            MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+            SB();
+            // K-step 2: multiply F0, fetch F1
+            RDA(a1, 3, 0); RDB(b1, 3, 0); RDB(b1, 3, 1); MF(a0, b0, 0, 0);
+            SB();
+            RDA(a1, 3, 1); RDA(a1, 3, 2); MF(a0, b0, 0, 1);
+            SB();
+            RDA(a1, 3, 3); MF(a0, b0, 1, 0);
+            SB();
+            MF(a0, b0, 1, 1); MF(a0, b0, 2, 0); MF(a0, b0, 2, 1); MF(a0, b0, 3, 0); MF(a0, b0, 3, 1);
+            SB();
+            if constexpr (NEXT) {
+                // stage s + 1 has landed for this wave (only the 4 newest loads, the activations of stage
+                // s + 2, may still be out), its reads of stage s are done; after the barrier that holds
+                // for every wave
+                if constexpr (NEXT2) wait_vm<4>(); else wait_vm<0>();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                SB();
+                sa = lds + ((s + 1) % kSlotsA) * kTile;
+                sb = lds + ((s + 1) & 1) * kTile;
+                // K-step 3: multiply F1, fetch F0 = K-step 0 of the next stage
+                RDA(a0, 0, 0); RDB(b0, 0, 0); RDB(b0, 0, 1); MF(a1, b1, 0, 0);
+                SB();
+                RDA(a0, 0, 1); RDA(a0, 0, 2); MF(a1, b1, 0, 1);
+                SB();
+                RDA(a0, 0, 3); MF(a1, b1, 1, 0);
+                SB();
+                MF(a1, b1, 1, 1); MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+                SB();
+            } else {
+                MF(a1, b1, 0, 0); MF(a1, b1, 0, 1); MF(a1, b1, 1, 0); MF(a1, b1, 1, 1);
+                MF(a1, b1, 2, 0); MF(a1, b1, 2, 1); MF(a1, b1, 3, 0); MF(a1, b1, 3, 1);
+            }
+        };
+        int s = 0;
+        for (; s + 2 < ns; ++s) stage(s, std::true_type{}, std::true_type{});
+        if (s + 1 < ns) { stage(s, std::true_type{}, std::false_type{}); ++s; }
+        stage(s, std::false_type{}, std::false_type{});
+
+        // ---- epilogue.  With the weight fragment as first MFMA operand, register v of lane l in
+        // sub-tile (i, j) is token t = m0 + 128 wm + 32 i + l % 32 and output channel
+        // n = n0 + 64 wn + 32 j + 8 (v / 4) + 4 (l / 32) + v % 4.  Each wave turns its 32 (t) x 64 (n)
+        // slab of sub-tile row i around in a private 8 KiB LDS region (256-byte rows, XOR-swizzled
+        // 16-byte chunks) so that 16 lanes cover one output row of the slab per store.  The slabs live
+        // in the third activation slot and the second weight slot: the next tile's first stages are
+        // already on their way into the others.
+        const int wr_t = lane & 31, wr_sw = wr_t & 15, wr_half = lane >> 5;
+        const int rd_r = lane >> 4, rd_c = lane & 15;
+        const int64_t n = cn0 + wn * 64 + rd_c * 4;      // this lane's four channels
+        const bool n_ok = n < g.N;                       // N % 4 == 0: all four or none
+        const int64_t t_lane = cm0 + wm * 128 + rd_r;    // + 32 i + 4 p
+        // what the epilogue reads from memory is requested before the next tile's stages, so that
+        // waiting for it does not wait for them (pinned: the compiler's wait then sits here)
+        v4f bs = {0.f, 0.f, 0.f, 0.f};
+        if (g.bias && n_ok) bs = *reinterpret_cast<const v4f*>(g.bias + n);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) asm volatile("" : "+v"(bs[c]));
+
+        // next tile of this workgroup
+        int nvb = vb + stride, ntm = 0, ntn = 0;
+        while (nvb < g.n_ids && !tile_of(g, nvb, ntm, ntn)) nvb += stride;
+        const bool more = nvb < g.n_ids;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();   // every wave is done reading the stage buffers
+        if (more) start_tile(ntm, ntn);
+
+        char* slab = lds + (wave < 4 ? 2 * kTile + wave * 8192 : kLdsB + kTile + (wave - 4) * 8192);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v4f o = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    *reinterpret_cast<v4f*>(slab + wr_t * 256 + (((8 * j + 2 * q + wr_half) ^ wr_sw) * 16)) = o;
+                }
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const int r = 4 * p + rd_r;
+                v4f o = *reinterpret_cast<const v4f*>(slab + r * 256 + ((rd_c ^ (r & 15)) * 16));
+                const int64_t t = t_lane + i * 32 + 4 * p;
+                if (t < g.T && n_ok) {
+                    o += bs;
+                    if constexpr (OUT_F16) {
+                        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                        h4 oh = {(_Float16)o[0], (_Float16)o[1], (_Float16)o[2], (_Float16)o[3]};
+                        __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out) + t * g.ldo + n));
+                    } else {
+                        __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(reinterpret_cast<float*>(g.out) + t * g.ldo + n));
+                    }
+                }
+            }
+        }
+        if (!more) break;
+        vb = nvb;
+        // stage 0 of the next tile has landed (interior tile: its 32 stores per wave may still drain)
+        if (ns > 1 && cm0 + BM <= g.T && cn0 + BN <= g.N) wait_vm<kStores + 4>();
+        else wait_vm<0>();
+    }
 #undef RDA
 #undef RDB
 #undef DMA_A
 #undef DMA_B
-
-    // ---- epilogue.  With the weight fragment as first MFMA operand, register v of lane l in
-    // sub-tile (i, j) is token t = m0 + 128 wm + 32 i + l % 32 and output channel
-    // n = n0 + 64 wn + 32 j + 8 (v / 4) + 4 (l / 32) + v % 4.  Each wave turns its 32 (t) x 64 (n)
-    // slab of sub-tile row i around in a private 8 KiB LDS region (256-byte rows, XOR-swizzled
-    // 16-byte chunks) so that 16 lanes cover one output row of the slab per store.
-    __syncthreads();  // every wave is done with the stage buffers
-    char* slab = lds + wave * 8192;
-    const int wr_t = lane & 31, wr_sw = wr_t & 15, wr_half = lane >> 5;
-    const int rd_r = lane >> 4, rd_c = lane & 15;
-    const int64_t n = n0 + wn * 64 + rd_c * 4;      // this lane's four channels
-    const bool n_ok = n < g.N;                      // N % 4 == 0: all four or none
-    const int64_t t_lane = m0 + wm * 128 + rd_r;    // + 32 i + 4 p
-    v4f bs = {0.f, 0.f, 0.f, 0.f};
-    if (g.bias && n_ok) bs = *reinterpret_cast<const v4f*>(g.bias + n);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                v4f o = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                *reinterpret_cast<v4f*>(slab + wr_t * 256 + (((8 * j + 2 * q + wr_half) ^ wr_sw) * 16)) = o;
-            }
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            const int r = 4 * p + rd_r;
-            v4f o = *reinterpret_cast<const v4f*>(slab + r * 256 + ((rd_c ^ (r & 15)) * 16));
-            const int64_t t = t_lane + i * 32 + 4 * p;
-            if (t < g.T && n_ok) {
-                o += bs;
-                if constexpr (OUT_F16) {
-                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                    h4 oh = {(_Float16)o[0], (_Float16)o[1], (_Float16)o[2], (_Float16)o[3]};
-                    __builtin_nontemporal_store(oh, reinterpret_cast<h4*>(reinterpret_cast<_Float16*>(g.out) + t * g.ldo + n));
-                } else {
-                    __builtin_nontemporal_store(o, reinterpret_cast<v4f*>(reinterpret_cast<float*>(g.out) + t * g.ldo + n));
-                }
-            }
-        }
-    }
 }
 #undef SB
 #undef MF
@@ -429,14 +480,20 @@ extern "C" int aweq_wonly_gemm(const void* X_hat, int64_t T, int64_t K, int64_t 
     g.n_main = (int)(patches_m * g.main_pn);
     g.n_patches = g.n_main + (g.tail_cols ? (int)cdiv(tiles_m, g.tail_pm) : 0);
     const int64_t rounds = cdiv(g.n_patches, wonly::kXcds);
-    const int64_t blocks = rounds * wonly::kXcds * g.per_patch;
-    if (blocks > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+    const int64_t ids = rounds * wonly::kXcds * g.per_patch;
+    if (ids > 0x7fffffffll) return AWEQ_ERR_SHAPE;
+    g.n_ids = (int)ids;
 
     const void* fn = out_dt == AWEQ_F16 ? reinterpret_cast<const void*>(wonly::gemm_f16_kernel<true>)
                                         : reinterpret_cast<const void*>(wonly::gemm_f16_kernel<false>);
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, wonly::kLds) != hipSuccess) return AWEQ_ERR_LAUNCH;
+    // persistent launch: one workgroup per compute unit (a multiple of 8, so that id % 8 stays the XCD)
+    int dev = 0, cus = 0;
+    if (device_cus(dev, cus) != AWEQ_OK || raise_lds_limit(fn, dev, wonly::kLds) != AWEQ_OK) return AWEQ_ERR_LAUNCH;
+    int64_t grid = (cus / wonly::kXcds) * wonly::kXcds;
+    if (grid < wonly::kXcds) grid = wonly::kXcds;
+    if (grid > ids) grid = ids;
     void* args[] = {&g};
-    if (hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(wonly::kThreads), args, wonly::kLds, st) != hipSuccess)
+    if (hipLaunchKernel(fn, dim3((unsigned)grid), dim3(wonly::kThreads), args, wonly::kLds, st) != hipSuccess)
         return AWEQ_ERR_LAUNCH;
     return launch_status();
 }
