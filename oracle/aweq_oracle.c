@@ -181,7 +181,7 @@ void orc_scales(const float* r_x, const float* r_w, int64_t K, int enable_awe,
 }
 
 /* The per-channel quantity of the difficulty definition the method replaces (Sec. 1 and Sec. 3.2:
- * "maximum absolute values of activations and weights"): m_i = max_t |x[t,i]| = max(|min_i|, |max_i|).
+ * difficulty measured by the largest magnitude of a channel, for activations and weights alike): m_i = max_t |x[t,i]| = max(|min_i|, |max_i|).
  * orc_scales applied to (m^X, m^W) instead of (r^X, r^W) gives that variant's scale in Eq. 10's form. */
 void orc_channel_absmax(const float* cmin, const float* cmax, int64_t K, float* m)
 {

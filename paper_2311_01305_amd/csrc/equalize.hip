@@ -17,7 +17,7 @@ __global__ __launch_bounds__(1024) void equalize_scales(
     float lo = INFINITY, hi = -INFINITY;
     for (int64_t k = threadIdx.x; k < K; k += blockDim.x) {
         // the per-channel quantity the scale balances: the channel range (Eq. 10), or - the definition the
-        // method replaces (Sec. 1, Sec. 3.2: maximum absolute values) - the channel's largest magnitude
+        // method replaces (Sec. 1, Sec. 3.2) - the channel's largest magnitude
         const float r_x = enable_awe == AWEQ_SCALE_ABSMAX ? fmaxf(fabsf(xmin[k]), fabsf(xmax[k])) : xmax[k] - xmin[k];
         const float r_w = enable_awe == AWEQ_SCALE_ABSMAX ? fmaxf(fabsf(wmin[k]), fabsf(wmax[k])) : wmax[k] - wmin[k];
         float sk = 1.0f;

@@ -195,7 +195,7 @@ def test_pitched_weight_through_the_pipeline(mods, orc):
 
 
 def test_absmax_scale_switch(mods, orc):
-    """AWEQ_SCALE_ABSMAX: the difficulty definition the method replaces (Sec. 1: maximum absolute values)
+    """AWEQ_SCALE_ABSMAX: the difficulty definition the method replaces (Sec. 1: a channel's largest magnitude)
     in Eq. 10's form, as a switch next to the method's own channel ranges."""
     B, pipeline, synth = mods
     wl = synth.scaled(synth.WORKLOADS[2], 640, [synth.Linear("fc", 128, 512)])
