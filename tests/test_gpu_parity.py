@@ -381,6 +381,28 @@ def test_quant_act_parity(B, orc, dtype, T, K):
     assert o["xq"].min() == -128 and o["xq"].max() == 127
 
 
+def test_quant_act_sums_are_deterministic_and_ignore_the_workspace_contents(B, orc):
+    """The sums go through per-slice partial buffers folded in a fixed order: two runs give the same bits
+    whatever the workspace held before (no atomics, nothing to clear), for one and for several column chunks."""
+    progress("quant_act determinism / workspace contents")
+    rng = np.random.default_rng(314)
+    for T, K in ((700, 512), (1300, 1544)):
+        X = (rng.standard_normal((T, K)) * 2).astype(np.float16)
+        inv_s = rng.uniform(0.3, 3.0, K).astype(np.float32)
+        outs = []
+        for fill in (0x00, 0xFF, 0x5A):
+            xq = torch.empty(B.aweq_panel_bytes(T, K), dtype=torch.int8, device=DEV)
+            rs, cs = e(T, dtype=torch.int32), e(K, dtype=torch.int64)
+            ws = torch.full((B.aweq_workspace_size(B.OP_QUANT_ACT, T, K),), fill, dtype=torch.uint8, device=DEV)
+            B.aweq_quant_act(dev(X), B.AWEQ_F16, T, K, K, dev(inv_s), dev(np.array([0.031], np.float32)),
+                             dev(np.array([131], np.int32)), xq, rs, cs, ws, None)
+            outs.append((host(xq).copy(), host(rs).copy(), host(cs).copy()))
+        for o in outs[1:]:
+            assert all(np.array_equal(a, b) for a, b in zip(o, outs[0]))
+        ref = orc.quant_act(X, inv_s, np.float32(0.031), 131)
+        assert np.array_equal(outs[0][1], ref["rowsum_x"]) and np.array_equal(outs[0][2], ref["colsum_xq"])
+
+
 def test_quant_act_quotient_paths(B, orc):
     """The division-free quotient must equal the true division: many Step values (random
     significands, including ones near a power of two and the all-ones guard), values on and
