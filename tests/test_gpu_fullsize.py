@@ -2,7 +2,8 @@
 OPT-6.7B-shaped block (q_proj: T = 262144 calibration tokens, 4096 x 4096, fp16) and of the
 LLaMA-7B-shaped block (down_proj: 4096 x 11008, heavy-tailed activations, three ragged column
 chunks in the activation quantizer, 172 K-panels in the GEMM) and of the LLaMA-65B-shaped block
-(gate_proj: 22016 x 8192, 86 output-tile columns, 23 GB of int32 output) run through the whole
+(gate_proj: 22016 x 8192, 86 output-tile columns, 23 GB of int32 output; down_proj: 8192 x 22016, 11.5 GB of
+activations, 344 K-panels: both distinct inputs of the configuration the benchmark's default line runs) run through the whole
 path on the GPU with the same driver the benchmark uses.
 
 The streaming stages are checked against the oracle over the FULL input (statistics, and the
@@ -25,7 +26,8 @@ def progress(msg):
     print(f"[gpu-fullsize] {msg}", flush=True)
 
 
-@pytest.fixture(scope="module", params=[(2, 0), (3, 6), (5, 4)], ids=["opt6.7b-q_proj", "llama7b-down_proj", "llama65b-gate_proj"])
+@pytest.fixture(scope="module", params=[(2, 0), (3, 6), (5, 4), (5, 6)],
+                ids=["opt6.7b-q_proj", "llama7b-down_proj", "llama65b-gate_proj", "llama65b-down_proj"])
 def run(request):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
