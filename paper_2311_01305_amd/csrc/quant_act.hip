@@ -295,9 +295,9 @@ __global__ __launch_bounds__(kQaBlock) void quant_act_kernel(
 }
 
 // Fold the per-slice column sums (fixed order, 64-bit) and the per-chunk row sums.  Blocks
-// [0, col_blocks) own 32 columns each: 8 groups of 32 threads take every 8th slice and meet in LDS;
-// the remaining blocks own 256 rows each.
-constexpr int kQaMergeCols = 32, kQaMergeParts = 8;
+// [0, col_blocks) own 32 columns each: 32 groups of 32 threads take every 32nd slice (few dependent loads
+// per thread: the kernel is bound by their latency) and meet in LDS; the remaining blocks own 1024 rows each.
+constexpr int kQaMergeCols = 32, kQaMergeParts = 32;
 __global__ __launch_bounds__(kQaMergeCols * kQaMergeParts) void quant_act_merge(
     const int32_t* __restrict__ colsum_part, int slices, int64_t K, long long* __restrict__ colsum_xq,
     const int32_t* __restrict__ rowsum_part, int chunks, int64_t T, int32_t* __restrict__ rowsum_x, int col_blocks)

@@ -228,12 +228,13 @@ __global__ __launch_bounds__(kStatsBlock) void col_stats_partial_f32(
 }
 
 // Fold the row slices and merge with what the caller already holds.  A block owns 32 columns;
-// its 8 groups of 32 threads take every 8th slice each and meet in LDS in a fixed order, so
+// its 32 groups of 32 threads take every 32nd slice each (the kernel is bound by the latency of these
+// few dependent loads, so they are spread over many threads) and meet in LDS in a fixed order, so
 // the fp64 sums are reproducible.
 // finalize: r = max - min per channel, R = tensor max - tensor min, p = r / R (Eq. 4) need every
 // block's columns, so each block adds its extremes to two keys and takes a ticket; the block that
 // draws the last ticket finds all columns merged and writes r, R, p.
-constexpr int kMergeCols = 32, kMergeParts = 8;
+constexpr int kMergeCols = 32, kMergeParts = 32;
 __global__ __launch_bounds__(kMergeCols * kMergeParts) void col_stats_merge(
     const float* __restrict__ pmin, const float* __restrict__ pmax, const double* __restrict__ psum,
     int slices, int64_t K, int64_t rows, float* cmin, float* cmax,
